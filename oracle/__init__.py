@@ -1,0 +1,218 @@
+"""ctypes front end of the CPU oracle (``probe_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: the tests, ``__graft_entry__.smoke()`` and the ``cpu_baseline``
+leg of ``bench.py`` may import this package; the product path never does.  It imports
+nothing from the HIP package and shares no code with it.
+
+The C file is compiled with gcc on first use (``build()``), into ``oracle/libprobe_oracle.so``.
+All arrays are numpy; bf16 tensors travel as ``uint16`` bit patterns.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+import threading
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "probe_oracle.c")
+_LIB = os.path.join(_HERE, "libprobe_oracle.so")
+_lock = threading.Lock()
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain C99 + OpenMP).  Returns the library path."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        cmd = ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-o", tmp, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    with _lock:
+        if _lib is None:
+            build()
+            lib = C.CDLL(_LIB)
+            lib.oracle_imbalance_ratio.restype = C.c_double
+            _lib = lib
+    return _lib
+
+
+def _p(a, ty):
+    if a is None:
+        return None
+    return a.ctypes.data_as(C.POINTER(ty))
+
+
+def _chk(a, dtype, shape=None):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    if shape is not None and tuple(a.shape) != tuple(shape):
+        raise ValueError("expected shape %s, got %s" % (shape, a.shape))
+    return a
+
+
+def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
+    """Widen bf16 bit patterns (uint16) exactly to float64."""
+    u = bits.astype(np.uint32) << np.uint32(16)
+    return u.view(np.float32).astype(np.float64)
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def _route(fn, x_bits, w_gate, bias, tokens_per_group, k, renormalize):
+    x_bits = _chk(x_bits, np.uint16)
+    T, H = x_bits.shape
+    w_gate = _chk(w_gate, np.float32)
+    E = w_gate.shape[0]
+    assert w_gate.shape == (E, H)
+    if bias is not None:
+        bias = _chk(bias, np.float32)
+        if bias.ndim == 1:
+            bias = bias.reshape(1, E)
+        G = bias.shape[0]
+        assert bias.shape == (G, E)
+    else:
+        G = 1
+    tpg = int(tokens_per_group) if tokens_per_group else max(T, 1)
+    logits = np.empty((T, E), np.float64)
+    probs = np.empty((T, E), np.float64)
+    idx = np.empty((T, k), np.int32)
+    w = np.empty((T, k), np.float64)
+    counts = np.empty((E,), np.int32)
+    rc = fn(_p(x_bits, C.c_uint16), _p(w_gate, C.c_float), _p(bias, C.c_float), G, tpg, T, H,
+            E, k, int(bool(renormalize)), _p(logits, C.c_double), _p(probs, C.c_double),
+            _p(idx, C.c_int32), _p(w, C.c_double), _p(counts, C.c_int32))
+    if rc != 0:
+        raise ValueError("oracle route failed: %d" % rc)
+    return dict(logits=logits, probs=probs, idx=idx, w=w, counts=counts)
+
+
+def route_topk(x_bits, w_gate, bias=None, tokens_per_group=None, k=2, renormalize=True):
+    """Router: logits, softmax over all experts, k largest, weights, counts n_e (fp64)."""
+    return _route(_load().oracle_route_topk, x_bits, w_gate, bias, tokens_per_group, k,
+                  renormalize)
+
+
+def predict_topk(h_prev_bits, w_gate_next, bias_next=None, tokens_per_group=None, k=2,
+                 renormalize=True):
+    """Lookahead predictor at its zero-initialised residual; ``counts`` is n-hat."""
+    return _route(_load().oracle_predict_topk, h_prev_bits, w_gate_next, bias_next,
+                  tokens_per_group, k, renormalize)
+
+
+def permute(topk_idx, rep_off, rep_slot, rep_weight, num_slots, x_bits=None):
+    """Sequential weighted round-robin assignment and stable grouping by slot."""
+    topk_idx = _chk(topk_idx, np.int32)
+    T, k = topk_idx.shape
+    rep_off = _chk(rep_off, np.int32)
+    E = rep_off.shape[0] - 1
+    rep_slot = _chk(rep_slot, np.int32)
+    rep_weight = _chk(rep_weight, np.int32)
+    S = int(num_slots)
+    N = T * k
+    H = 0
+    xp = None
+    if x_bits is not None:
+        x_bits = _chk(x_bits, np.uint16)
+        H = x_bits.shape[1]
+        assert x_bits.shape[0] == T
+        xp = np.empty((N, H), np.uint16)
+    slot_counts = np.empty((S,), np.int32)
+    slot_offsets = np.empty((S + 1,), np.int32)
+    row_pair = np.empty((N,), np.int32)
+    pair_row = np.empty((T, k), np.int32)
+    n_local = np.zeros((1,), np.int32)
+    rc = _load().oracle_permute(_p(topk_idx, C.c_int32), _p(rep_off, C.c_int32),
+                                _p(rep_slot, C.c_int32), _p(rep_weight, C.c_int32), S,
+                                _p(x_bits, C.c_uint16), T, H, E, k, _p(slot_counts, C.c_int32),
+                                _p(slot_offsets, C.c_int32), _p(row_pair, C.c_int32),
+                                _p(pair_row, C.c_int32), _p(xp, C.c_uint16),
+                                _p(n_local, C.c_int32))
+    if rc != 0:
+        raise ValueError("oracle permute failed: %d" % rc)
+    return dict(slot_counts=slot_counts, slot_offsets=slot_offsets, row_pair=row_pair,
+                pair_row=pair_row, xp=xp, n_local=int(n_local[0]))
+
+
+def grouped_ffn(xp_bits, slot_offsets, w13_list, w2_list, rows=None):
+    """SwiGLU expert FFN for the rows listed (all rows below slot_offsets[-1] if None).
+
+    Returns fp64 [len(rows), H]."""
+    xp_bits = _chk(xp_bits, np.uint16)
+    H = xp_bits.shape[1]
+    slot_offsets = _chk(slot_offsets, np.int32)
+    S = slot_offsets.shape[0] - 1
+    assert len(w13_list) == S and len(w2_list) == S
+    w13_list = [_chk(w, np.uint16) for w in w13_list]
+    w2_list = [_chk(w, np.uint16) for w in w2_list]
+    F = w2_list[0].shape[1] if S else 1
+    for a, b in zip(w13_list, w2_list):
+        assert a.shape == (2 * F, H) and b.shape == (H, F)
+    if rows is None:
+        rows = np.arange(int(slot_offsets[-1]), dtype=np.int32)
+    rows = _chk(rows, np.int32)
+    if rows.size:
+        assert rows.min() >= 0 and rows.max() < xp_bits.shape[0]
+    PT = C.POINTER(C.c_uint16)
+    a13 = (PT * max(S, 1))(*[_p(w, C.c_uint16) for w in w13_list])
+    a2 = (PT * max(S, 1))(*[_p(w, C.c_uint16) for w in w2_list])
+    y = np.zeros((rows.shape[0], H), np.float64)
+    rc = _load().oracle_grouped_ffn(_p(xp_bits, C.c_uint16), _p(slot_offsets, C.c_int32), a13,
+                                    a2, S, H, F, _p(rows, C.c_int32), int(rows.shape[0]),
+                                    _p(y, C.c_double))
+    if rc != 0:
+        raise ValueError("oracle grouped_ffn failed: %d" % rc)
+    return y
+
+
+def combine(y, pair_row, w):
+    """Gate-weighted sum over a token's local pairs, ascending top-k position (fp64)."""
+    y = _chk(y, np.float64)
+    H = y.shape[1]
+    pair_row = _chk(pair_row, np.int32)
+    T, k = pair_row.shape
+    w = _chk(w, np.float64, (T, k))
+    if pair_row.size:
+        assert pair_row.max() < y.shape[0]
+    out = np.empty((T, H), np.float64)
+    rc = _load().oracle_combine(_p(y, C.c_double), _p(pair_row, C.c_int32), _p(w, C.c_double),
+                                T, H, k, _p(out, C.c_double))
+    if rc != 0:
+        raise ValueError("oracle combine failed: %d" % rc)
+    return out
+
+
+def imbalance_ratio(rank_load) -> float:
+    """Eq. 1: max rank load over mean rank load."""
+    rank_load = _chk(rank_load, np.float64)
+    return float(_load().oracle_imbalance_ratio(_p(rank_load, C.c_double), int(rank_load.size)))
+
+
+def topk_overlap(pred_idx, true_idx) -> float:
+    """Mean over tokens of |pred_k intersect true_k| / k (the predictor's top-k accuracy)."""
+    pred_idx = np.asarray(pred_idx)
+    true_idx = np.asarray(true_idx)
+    T, k = true_idx.shape
+    hit = 0
+    for t in range(T):
+        hit += len(set(pred_idx[t].tolist()) & set(true_idx[t].tolist()))
+    return hit / float(max(T, 1) * k)
+
+
+def moe_layer(x_bits, w_gate, bias, tokens_per_group, k, renormalize, plan, w13_list, w2_list):
+    """Whole layer: route -> permute -> FFN -> combine, nothing rounded in between."""
+    r = route_topk(x_bits, w_gate, bias, tokens_per_group, k, renormalize)
+    p = permute(r["idx"], plan["rep_off"], plan["rep_slot"], plan["rep_weight"],
+                plan["num_slots"], x_bits)
+    y = grouped_ffn(p["xp"], p["slot_offsets"], w13_list, w2_list)
+    out = combine(y, p["pair_row"], r["w"])
+    return dict(route=r, permute=p, y=y, out=out)
