@@ -1,0 +1,195 @@
+/*
+ * probe.h - C ABI of libprobe: one GPU's share of an expert-parallel MoE layer on MI355X
+ * (gfx950), after PROBE (arxiv 2602.00509).
+ *
+ * The five calls are the steps of the layer's main track (Sec. 4.1 of the paper) that run
+ * on one GPU between the two all-to-all exchanges, plus the lookahead predictor of the
+ * auxiliary track (Sec. 4.2):
+ *
+ *   probe_route_topk    router of layer L: logits W_L h + b_L, softmax, k largest
+ *   probe_predict_topk  gate-initialised lookahead predictor (Eq. 7, frozen prior term)
+ *   probe_permute       group (token, top-k position) pairs by the expert replica that the
+ *                       balance plan (placement P, assignment A; Sec. 3.1, Sec. 4.3) gives them
+ *   probe_grouped_ffn   grouped SwiGLU expert FFN over native + replicated experts
+ *                       (E_r U Delta_r, Sec. 3.2)
+ *   probe_combine       gate-weighted sum of a token's expert outputs (local part of the
+ *                       combine step)
+ *
+ * Conventions for every call
+ *   - Every pointer marked "device" is caller-owned device memory; the library never
+ *     allocates, frees, synchronises or copies to the host inside these calls.  Sizes that
+ *     depend on the data (rows per slot, number of local rows) exist only in device memory,
+ *     so a sequence of calls can be recorded in a HIP graph (Sec. 2.3: no host-device
+ *     synchronisation on the serving path).
+ *   - `stream` is the caller's hipStream_t passed as void* (NULL = the default stream).
+ *   - bf16 tensors are raw 16-bit patterns, row-major, innermost dimension contiguous.
+ *   - Device pointers must be 16-byte aligned unless stated otherwise.
+ *   - Return value: PROBE_OK or a negative error code.  Arguments are validated on the host
+ *     before anything is launched; a failing call launches nothing.
+ *     probe_last_error_string() describes the last failure on the calling thread.
+ *   - `workspace` is device scratch of at least probe_<name>_workspace_bytes(...) bytes; its
+ *     contents are undefined on entry and on return.  Calls that share a workspace must be
+ *     ordered on one stream.
+ *
+ * Vocabulary: T tokens, H hidden size, E routed experts, k experts per token, F expert FFN
+ * width, S weight slots on this GPU (one expert copy each), pair p = t*k + s (token t,
+ * top-k position s), N = T*k pairs.
+ */
+#ifndef PROBE_H_
+#define PROBE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PROBE_OK            0
+#define PROBE_EINVAL       -1  /* null pointer, non-positive dimension, k > E, bad plan size */
+#define PROBE_EUNSUPPORTED -2  /* shape outside the kernels' limits (see each call)          */
+#define PROBE_EALIGN       -3  /* a device pointer is not 16-byte aligned                     */
+#define PROBE_EWORKSPACE   -4  /* workspace is NULL or too small                              */
+#define PROBE_EHIP         -5  /* the HIP runtime rejected a launch                           */
+
+/* Limits of this build. */
+#define PROBE_MAX_EXPERTS 256  /* E                         */
+#define PROBE_MAX_TOPK      8  /* k                         */
+#define PROBE_MAX_SLOTS  1024  /* S                         */
+
+/* Text of the last error raised on the calling thread ("" if none). Host pointer, owned by
+ * the library, valid until the next failing call on the same thread. */
+const char* probe_last_error_string(void);
+
+/* Library version, e.g. "0.1". Host pointer, static storage. */
+const char* probe_version(void);
+
+/* ------------------------------------------------------------------ route / predict ---
+ *
+ * Router of Sec. 4.2: l[t,e] = sum_h x[t,h] * w_gate[e,h] + bias[g(t),e];
+ * p = softmax of l over all E experts; the k experts with the largest logits in descending
+ * order (exact ties: lower expert index first); topk_w[t,s] = p[t, topk_idx[t,s]], divided
+ * by their sum over s when `renormalize` is non-zero; expert_counts[e] = number of pairs
+ * routed to e (n_e of Table 1, sum_e n_e = T*k).
+ *
+ *   x_bf16         device, bf16 [T,H]
+ *   w_gate         device, fp32 [E,H]
+ *   bias           device, fp32 [bias_groups,E], or NULL for no bias
+ *   bias_groups    G >= 1; token t uses bias row min(t / tokens_per_group, G-1).  G = 1 is
+ *                  the paper's single b_L; G > 1 lets one call carry a hot set that moves
+ *                  between chunks of tokens.
+ *   topk_idx       device, int32 [T,k]       (out)
+ *   topk_w         device, fp32  [T,k]       (out)
+ *   probs          device, fp32  [T,E] or NULL (out, full softmax)
+ *   expert_counts  device, int32 [E] or NULL (out)
+ *
+ * Arithmetic: x is bf16 exactly, w_gate is used at full fp32 precision (three bf16 planes
+ * on the matrix cores), accumulation in fp32.
+ * Limits: 1 <= k <= 8, k <= E <= 256, H % 32 == 0, T >= 0 (T = 0 writes only zero counts).
+ */
+size_t probe_route_topk_workspace_bytes(int T, int H, int E, int k);
+
+int probe_route_topk(const void* x_bf16, const float* w_gate, const float* bias,
+                     int bias_groups, int tokens_per_group, int T, int H, int E, int k,
+                     int renormalize, int32_t* topk_idx, float* topk_w, float* probs,
+                     int32_t* expert_counts, void* workspace, size_t workspace_bytes,
+                     void* stream);
+
+/* Gate-initialised lookahead predictor (Eq. 7) with its trainable residual at the zero
+ * initialisation the paper prescribes: the cloned router (w_gate_next, bias_next) of layer L
+ * applied to the hidden states h_prev of layer L-1.  Same arguments, limits and arithmetic
+ * as probe_route_topk; pred_counts is the predicted per-expert workload n-hat that the
+ * planner consumes (Sec. 4.3).  The prediction never changes dispatch. */
+size_t probe_predict_topk_workspace_bytes(int T, int H, int E, int k);
+
+int probe_predict_topk(const void* h_prev_bf16, const float* w_gate_next,
+                       const float* bias_next, int bias_groups, int tokens_per_group, int T,
+                       int H, int E, int k, int renormalize, int32_t* pred_idx, float* pred_w,
+                       float* probs, int32_t* pred_counts, void* workspace,
+                       size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------- permute ---
+ *
+ * The balance plan as this GPU sees it (Sec. 3.1: n_{e,r} with sum_r n_{e,r} = n_e; Sec. 4.3:
+ * n_{e,r} > 0 only where P_{r,e} = 1).  Expert e owns replicas rep_off[e] .. rep_off[e+1]-1.
+ * Replica i lives in local weight slot rep_slot[i] in [0,S), or on another GPU (-1), and
+ * receives rep_weight[i] out of every P_e = sum of e's weights consecutive arrivals
+ * (weighted round-robin in pair order; P_e >= 1, weights >= 0).  The struct itself is host
+ * memory; the three arrays are device memory, int32.
+ */
+typedef struct {
+  const int32_t* rep_off;    /* device [E+1] */
+  const int32_t* rep_slot;   /* device [R], R = rep_off[E] */
+  const int32_t* rep_weight; /* device [R] */
+  int32_t num_slots;         /* S */
+} probe_plan;
+
+/*
+ * Pairs are visited in ascending p = t*k + s.  The j-th arrival (from 0) of expert e goes to
+ * the first of its replicas whose cumulative weight exceeds j mod P_e.  Pairs sent to a local
+ * slot are grouped by slot, ascending p inside a slot; rows are the groups in slot order.
+ *
+ *   topk_idx      device, int32 [T,k], values in [0,E)
+ *   x_bf16        device, bf16 [T,H]
+ *   slot_counts   device, int32 [S]    (out) rows per slot
+ *   slot_offsets  device, int32 [S+1]  (out) exclusive prefix sum; [S] = n_local
+ *   row_pair      device, int32 [T*k]  (out) pair of each row; entries >= n_local are -1
+ *   pair_row      device, int32 [T,k]  (out) row of each pair, -1 = computed on another GPU
+ *   xp_bf16       device, bf16 [T*k,H] (out) xp[row] = x[row_pair[row] / k]; rows >= n_local
+ *                 are not written
+ *   n_local       device, int32 [1]    (out)
+ *
+ * Integer outputs and row copies are exact.  Limits: E <= 256, k <= 8, S <= 1024, H % 8 == 0,
+ * T*k < 2^31.  An out-of-range expert id or slot id is undefined behaviour.
+ */
+size_t probe_permute_workspace_bytes(int T, int E, int k, int S);
+
+int probe_permute(const int32_t* topk_idx, const probe_plan* plan, const void* x_bf16, int T,
+                  int H, int E, int k, int32_t* slot_counts, int32_t* slot_offsets,
+                  int32_t* row_pair, int32_t* pair_row, void* xp_bf16, int32_t* n_local,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------ grouped FFN ---
+ *
+ * Grouped GEMM over the experts resident on this GPU (Sec. 3.2, T_comp over E_r U Delta_r).
+ * For every slot s and every row r in [slot_offsets[s], slot_offsets[s+1]):
+ *     a = W1_s xp[r],  c = W3_s xp[r],  h = silu(a) * c,  y[r] = W2_s h
+ *
+ *   xp_bf16       device, bf16 [max_rows,H]
+ *   slot_offsets  device, int32 [S+1], non-decreasing, slot_offsets[S] <= max_rows
+ *   w13_ptrs      device array [S] of device pointers, each bf16 [2F,H]: rows 0..F-1 are W1
+ *                 (gate projection), rows F..2F-1 are W3 (up projection)
+ *   w2_ptrs       device array [S] of device pointers, each bf16 [H,F]
+ *   max_rows      capacity of xp / y in rows (T*k); sizes the launch, not the work
+ *   y_bf16        device, bf16 [max_rows,H] (out); rows >= slot_offsets[S] are not written
+ *
+ * bf16 inputs, fp32 accumulation on the matrix cores, h rounded to bf16 between the two
+ * GEMMs, bf16 output.  An empty slot does no work and its weights are not read.
+ * Limits: H % 64 == 0, F % 64 == 0, 1 <= S <= 1024.
+ */
+size_t probe_grouped_ffn_workspace_bytes(int S, int H, int F, int max_rows);
+
+int probe_grouped_ffn(const void* xp_bf16, const int32_t* slot_offsets,
+                      const void* const* w13_ptrs, const void* const* w2_ptrs, int S, int H,
+                      int F, int max_rows, void* y_bf16, void* workspace,
+                      size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------- combine ---
+ *
+ * out[t,:] = sum over s ascending with pair_row[t,s] >= 0 of topk_w[t,s] * y[pair_row[t,s],:]
+ * (fp32 accumulation, one rounding to bf16).  A token with no local pair gives a zero row.
+ *
+ *   y_bf16    device, bf16 [n_rows,H], n_rows > max(pair_row)
+ *   pair_row  device, int32 [T,k]
+ *   topk_w    device, fp32 [T,k]
+ *   out_bf16  device, bf16 [T,H] (out)
+ *
+ * Limits: H % 8 == 0, 1 <= k <= 8.  No workspace.
+ */
+int probe_combine(const void* y_bf16, const int32_t* pair_row, const float* topk_w, int T,
+                  int H, int k, void* out_bf16, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PROBE_H_ */

@@ -1,0 +1,276 @@
+// probe_permute: plan-driven grouping of (token, top-k position) pairs by weight slot.
+//
+// The sequential definition (walk the pairs in order, the j-th arrival of an expert goes to a
+// replica by weighted round-robin, append to the slot's list) is reproduced exactly without
+// atomics: a pair's destination row follows from (expert e, arrival rank j) alone.
+//
+//   1. hist     each wave counts the experts of its own contiguous segment of pairs
+//               (LDS counters, one set per wave)                        -> seg_hist[U][E]
+//   2. scan     per expert, exclusive scan over segments                 -> seg_hist becomes
+//               seg_base; n_e; closed-form rows per replica; prefix sum over slots
+//               -> slot_counts, slot_offsets, n_local
+//   3. index    every wave re-walks its segment, ranks each pair among equal experts with
+//               wave ballots, and computes slot and row analytically     -> pair_row, row_pair
+//   4. scatter  one thread per 16-byte chunk of a token row: read x once, write it to each of
+//               the token's local rows                                   -> xp
+//
+// Steps 1-3 touch only T*k integers; step 4 carries the HBM traffic (T*H*2 bytes read at
+// most, n_local*H*2 written).
+#include "common.hpp"
+
+namespace probe {
+
+constexpr int kPermWaves = 4;                 // waves per workgroup in steps 1 and 3
+constexpr int kSegPairs = 1024;               // pairs per wave segment
+constexpr int kSegIters = kSegPairs / kWave;  // 16 wave-wide iterations per segment
+
+__device__ __forceinline__ uint64_t lanemask_lt() {
+  int l = lane_id();
+  return l == 0 ? 0ull : (~0ull >> (64 - l));
+}
+
+// Lanes of the wave holding the same 8-bit key as this lane (inactive lanes excluded by
+// passing valid = false; they get an empty mask).
+__device__ __forceinline__ uint64_t match_key8(int key, bool valid) {
+  uint64_t m = __ballot(valid);
+#pragma unroll
+  for (int b = 0; b < 8; ++b) {
+    uint64_t bal = __ballot(valid && ((key >> b) & 1));
+    m &= ((key >> b) & 1) ? bal : ~bal;
+  }
+  return valid ? m : 0ull;
+}
+
+// Step 1.
+__global__ __launch_bounds__(kPermWaves* kWave) void permute_hist_kernel(
+    const int32_t* __restrict__ topk_idx, int N, int E, int32_t* __restrict__ seg_hist) {
+  __shared__ int32_t cnt_mem[kPermWaves][PROBE_MAX_EXPERTS];
+  int w = threadIdx.x / kWave, lane = lane_id();
+  volatile int32_t* cnt_w = cnt_mem[w];  // volatile: keep every lane's read before the leader's update
+  for (int e = lane; e < E; e += kWave) cnt_w[e] = 0;
+  int seg = blockIdx.x * kPermWaves + w;
+  long base = static_cast<long>(seg) * kSegPairs;
+  // same-wave LDS accesses execute in program order; no barrier needed for a wave's own row
+  for (int it = 0; it < kSegIters; ++it) {
+    long p = base + it * kWave + lane;
+    int e = p < N ? topk_idx[p] : -1;
+    bool valid = static_cast<unsigned>(e) < static_cast<unsigned>(E);  // bad ids count nowhere
+    uint64_t m = match_key8(e, valid);
+    if (valid && (m & lanemask_lt()) == 0) cnt_w[e] += __popcll(m);
+  }
+  if (base < N)
+    for (int e = lane; e < E; e += kWave) seg_hist[static_cast<long>(seg) * E + e] = cnt_w[e];
+}
+
+// Step 2.  One workgroup of 256 threads; thread e owns expert e.
+__global__ __launch_bounds__(256) void permute_scan_kernel(
+    int32_t* __restrict__ seg_hist /* in: counts, out: exclusive bases */, int U, int E,
+    const int32_t* __restrict__ rep_off, const int32_t* __restrict__ rep_slot,
+    const int32_t* __restrict__ rep_weight, int S, int32_t* __restrict__ slot_counts,
+    int32_t* __restrict__ slot_offsets, int32_t* __restrict__ n_local) {
+  __shared__ int32_t sc[PROBE_MAX_SLOTS];
+  __shared__ int32_t wave_tot[4];
+  int tid = threadIdx.x;
+  for (int s = tid; s < S; s += 256) sc[s] = 0;
+  __syncthreads();
+  if (tid < E) {
+    int run = 0;
+    for (int u = 0; u < U; ++u) {
+      long i = static_cast<long>(u) * E + tid;
+      int c = seg_hist[i];
+      seg_hist[i] = run;
+      run += c;
+    }
+    // rows each replica of this expert receives: floor(n/P) w_i + clamp(n mod P - c_{i-1}, 0, w_i)
+    int lo = rep_off[tid], hi = rep_off[tid + 1];
+    int P = 0;
+    for (int i = lo; i < hi; ++i) P += rep_weight[i];
+    if (P > 0) {
+      int full = run / P, rem = run - full * P, cum = 0;
+      for (int i = lo; i < hi; ++i) {
+        int wgt = rep_weight[i];
+        int part = min(max(rem - cum, 0), wgt);
+        int slot = rep_slot[i];
+        if (slot >= 0 && slot < S) sc[slot] = full * wgt + part;
+        cum += wgt;
+      }
+    }
+  }
+  __syncthreads();
+  // exclusive prefix sum over S <= 1024 slots: 4 consecutive slots per thread
+  int v[4], local = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    int s = tid * 4 + i;
+    v[i] = s < S ? sc[s] : 0;
+    local += v[i];
+  }
+  int incl = local;
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    int o = __shfl_up(incl, d, kWave);
+    if (lane_id() >= d) incl += o;
+  }
+  if (lane_id() == kWave - 1) wave_tot[tid / kWave] = incl;
+  __syncthreads();
+  int wave_base = 0;
+  for (int i = 0; i < tid / kWave; ++i) wave_base += wave_tot[i];
+  int excl = wave_base + incl - local;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    int s = tid * 4 + i;
+    if (s < S) {
+      slot_counts[s] = v[i];
+      slot_offsets[s] = excl;
+    }
+    excl += v[i];
+  }
+  if (tid == 255) {
+    slot_offsets[S] = excl;
+    n_local[0] = excl;
+  }
+}
+
+// Step 3.
+__global__ __launch_bounds__(kPermWaves* kWave) void permute_index_kernel(
+    const int32_t* __restrict__ topk_idx, int N, int E, const int32_t* __restrict__ seg_base,
+    const int32_t* __restrict__ rep_off, const int32_t* __restrict__ rep_slot,
+    const int32_t* __restrict__ rep_weight, const int32_t* __restrict__ slot_offsets, int S,
+    int32_t* __restrict__ pair_row, int32_t* __restrict__ row_pair) {
+  __shared__ int32_t cnt_mem[kPermWaves][PROBE_MAX_EXPERTS];
+  int w = threadIdx.x / kWave, lane = lane_id();
+  volatile int32_t* cnt_w = cnt_mem[w];  // volatile: keep every lane's read before the leader's update
+  int seg = blockIdx.x * kPermWaves + w;
+  long base = static_cast<long>(seg) * kSegPairs;
+  if (base < N)
+    for (int e = lane; e < E; e += kWave) cnt_w[e] = seg_base[static_cast<long>(seg) * E + e];
+  int n_loc = slot_offsets[S];
+  for (int it = 0; it < kSegIters; ++it) {
+    long p = base + it * kWave + lane;
+    int e = p < N ? topk_idx[p] : -1;
+    bool valid = static_cast<unsigned>(e) < static_cast<unsigned>(E);
+    uint64_t m = match_key8(e, valid);
+    if (p < N && !valid) {  // expert id out of range: the pair is computed nowhere on this GPU
+      pair_row[p] = -1;
+      if (p >= n_loc) row_pair[p] = -1;
+    }
+    if (valid) {
+      int before = __popcll(m & lanemask_lt());
+      int j = cnt_w[e] + before;                       // arrival rank of this pair for expert e
+      int lo = rep_off[e], hi = rep_off[e + 1];
+      int P = 0;
+      for (int i = lo; i < hi; ++i) P += rep_weight[i];
+      int row = -1;
+      if (P > 0) {
+        int full = j / P, u = j - full * P, cum = 0;
+        for (int i = lo; i < hi; ++i) {
+          int wgt = rep_weight[i];
+          if (u < cum + wgt) {
+            int slot = rep_slot[i];
+            if (slot >= 0 && slot < S) row = slot_offsets[slot] + full * wgt + (u - cum);
+            if (row >= N) row = -1;  // only an inconsistent plan (two replicas in one slot) gets here
+            break;
+          }
+          cum += wgt;
+        }
+      }
+      pair_row[p] = row;
+      if (row >= 0) row_pair[row] = static_cast<int32_t>(p);
+      if (p >= n_loc) row_pair[p] = -1;
+    }
+    // all lanes of a key have read the counter above; the key's first lane now advances it
+    if (valid && (m & lanemask_lt()) == 0) cnt_w[e] += __popcll(m);
+  }
+}
+
+// Step 4.
+template <int K>
+__global__ __launch_bounds__(256) void permute_scatter_kernel(const u32x4* __restrict__ x,
+                                                              const int32_t* __restrict__ pair_row,
+                                                              long total_chunks, int chunks_per_row,
+                                                              u32x4* __restrict__ xp) {
+  long gid = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (gid >= total_chunks) return;
+  int t = static_cast<int>(gid / chunks_per_row);
+  int c = static_cast<int>(gid - static_cast<long>(t) * chunks_per_row);
+  int rows[K];
+  bool any = false;
+#pragma unroll
+  for (int s = 0; s < K; ++s) {
+    rows[s] = pair_row[static_cast<long>(t) * K + s];
+    any |= rows[s] >= 0;
+  }
+  if (!any) return;
+  u32x4 v = __builtin_nontemporal_load(&x[gid]);
+#pragma unroll
+  for (int s = 0; s < K; ++s)
+    if (rows[s] >= 0) __builtin_nontemporal_store(v, &xp[static_cast<long>(rows[s]) * chunks_per_row + c]);
+}
+
+static int num_segments(long N) { return static_cast<int>((N + kSegPairs - 1) / kSegPairs); }
+
+}  // namespace probe
+
+extern "C" size_t probe_permute_workspace_bytes(int T, int E, int k, int S) {
+  (void)S;
+  if (T < 0 || E <= 0 || k <= 0) return 0;
+  long N = static_cast<long>(T) * k;
+  int U = probe::num_segments(N);
+  return probe::align_up(static_cast<size_t>(U > 0 ? U : 1) * E * sizeof(int32_t), 256);
+}
+
+extern "C" int probe_permute(const int32_t* topk_idx, const probe_plan* plan, const void* x_bf16,
+                             int T, int H, int E, int k, int32_t* slot_counts,
+                             int32_t* slot_offsets, int32_t* row_pair, int32_t* pair_row,
+                             void* xp_bf16, int32_t* n_local, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+  using namespace probe;
+  PROBE_REQUIRE(T >= 0 && H > 0 && E > 0 && k > 0, PROBE_EINVAL,
+                "probe_permute: bad dims T=%d H=%d E=%d k=%d", T, H, E, k);
+  PROBE_REQUIRE(plan != nullptr, PROBE_EINVAL, "probe_permute: plan is NULL");
+  int S = plan->num_slots;
+  PROBE_REQUIRE(S >= 1, PROBE_EINVAL, "probe_permute: plan->num_slots=%d", S);
+  PROBE_REQUIRE(E <= PROBE_MAX_EXPERTS && k <= PROBE_MAX_TOPK && S <= PROBE_MAX_SLOTS && H % 8 == 0,
+                PROBE_EUNSUPPORTED,
+                "probe_permute: needs E <= %d, k <= %d, S <= %d, H %% 8 == 0 (E=%d k=%d S=%d H=%d)",
+                PROBE_MAX_EXPERTS, PROBE_MAX_TOPK, PROBE_MAX_SLOTS, E, k, S, H);
+  PROBE_REQUIRE(static_cast<long>(T) * k < (1l << 31), PROBE_EUNSUPPORTED, "probe_permute: T*k >= 2^31");
+  PROBE_REQUIRE(plan->rep_off && plan->rep_slot && plan->rep_weight, PROBE_EINVAL,
+                "probe_permute: plan array is NULL");
+  PROBE_REQUIRE(slot_counts && slot_offsets && n_local, PROBE_EINVAL, "probe_permute: null output");
+  PROBE_REQUIRE(T == 0 || (topk_idx && x_bf16 && row_pair && pair_row && xp_bf16), PROBE_EINVAL,
+                "probe_permute: null pointer");
+  PROBE_REQUIRE(aligned16(x_bf16) && aligned16(xp_bf16), PROBE_EALIGN,
+                "probe_permute: x/xp must be 16-byte aligned");
+  PROBE_REQUIRE(workspace && workspace_bytes >= probe_permute_workspace_bytes(T, E, k, S),
+                PROBE_EWORKSPACE, "probe_permute: workspace too small (%zu < %zu)", workspace_bytes,
+                probe_permute_workspace_bytes(T, E, k, S));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  int N = T * k;
+  int U = num_segments(N);
+  int32_t* seg = static_cast<int32_t*>(workspace);
+  int seg_blocks = (U + kPermWaves - 1) / kPermWaves;
+  if (U > 0)
+    hipLaunchKernelGGL(permute_hist_kernel, dim3(seg_blocks), dim3(kPermWaves * kWave), 0, st, topk_idx, N,
+                       E, seg);
+  hipLaunchKernelGGL(permute_scan_kernel, dim3(1), dim3(256), 0, st, seg, U, E, plan->rep_off,
+                     plan->rep_slot, plan->rep_weight, S, slot_counts, slot_offsets, n_local);
+  if (U > 0) {
+    hipLaunchKernelGGL(permute_index_kernel, dim3(seg_blocks), dim3(kPermWaves * kWave), 0, st, topk_idx,
+                       N, E, seg, plan->rep_off, plan->rep_slot, plan->rep_weight, slot_offsets, S,
+                       pair_row, row_pair);
+    int cpr = H / 8;
+    long total = static_cast<long>(T) * cpr;
+    unsigned grid = static_cast<unsigned>((total + 255) / 256);
+    const u32x4* x = static_cast<const u32x4*>(x_bf16);
+    u32x4* xp = static_cast<u32x4*>(xp_bf16);
+#define PROBE_SCATTER_CASE(K) \
+  case K: hipLaunchKernelGGL(permute_scatter_kernel<K>, dim3(grid), dim3(256), 0, st, x, pair_row, total, cpr, xp); break;
+    switch (k) {
+      PROBE_SCATTER_CASE(1) PROBE_SCATTER_CASE(2) PROBE_SCATTER_CASE(3) PROBE_SCATTER_CASE(4)
+      PROBE_SCATTER_CASE(5) PROBE_SCATTER_CASE(6) PROBE_SCATTER_CASE(7) PROBE_SCATTER_CASE(8)
+    }
+#undef PROBE_SCATTER_CASE
+  }
+  return check_launch("probe_permute");
+}

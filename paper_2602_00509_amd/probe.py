@@ -1,0 +1,270 @@
+"""Thin ctypes binding of libprobe.so (include/probe.h).
+
+Argument marshalling only: every step of the layer runs in the HIP kernels of the library.
+PyTorch appears here for device memory (tensors as buffers) and streams, nothing else.  There
+is no CPU fallback: if the library is missing or a call fails, an exception is raised.
+
+Function names follow the C entry points (``route_topk`` -> ``probe_route_topk`` ...).
+Outputs and workspaces may be passed in (``out=...``, ``workspace=...``) so that a caller can
+pre-allocate everything; otherwise they are allocated with torch on the input's device.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libprobe.so")
+_lib = None
+
+MAX_EXPERTS, MAX_TOPK, MAX_SLOTS = 256, 8, 1024
+
+
+class ProbeError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__("libprobe error %d: %s" % (code, text))
+        self.code = code
+
+
+class _Plan(C.Structure):
+    _fields_ = [("rep_off", C.c_void_p), ("rep_slot", C.c_void_p), ("rep_weight", C.c_void_p),
+                ("num_slots", C.c_int32)]
+
+
+def lib():
+    """Load libprobe.so (built in-tree by build.py); raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                "%s not found: build it with `python -m paper_2602_00509_amd.build` "
+                "(there is no fallback path)" % LIB_PATH)
+        L = C.CDLL(LIB_PATH)
+        L.probe_last_error_string.restype = C.c_char_p
+        L.probe_version.restype = C.c_char_p
+        for name in ("probe_route_topk_workspace_bytes", "probe_predict_topk_workspace_bytes"):
+            getattr(L, name).restype = C.c_size_t
+            getattr(L, name).argtypes = [C.c_int] * 4
+        L.probe_permute_workspace_bytes.restype = C.c_size_t
+        L.probe_permute_workspace_bytes.argtypes = [C.c_int] * 4
+        L.probe_grouped_ffn_workspace_bytes.restype = C.c_size_t
+        L.probe_grouped_ffn_workspace_bytes.argtypes = [C.c_int] * 4
+        route_args = ([C.c_void_p] * 3 + [C.c_int] * 7 + [C.c_void_p] * 5 + [C.c_size_t, C.c_void_p])
+        L.probe_route_topk.argtypes = route_args
+        L.probe_predict_topk.argtypes = route_args
+        L.probe_permute.argtypes = ([C.c_void_p, C.POINTER(_Plan), C.c_void_p] + [C.c_int] * 4 +
+                                    [C.c_void_p] * 7 + [C.c_size_t, C.c_void_p])
+        L.probe_grouped_ffn.argtypes = ([C.c_void_p] * 4 + [C.c_int] * 4 + [C.c_void_p] * 2 +
+                                        [C.c_size_t, C.c_void_p])
+        L.probe_combine.argtypes = [C.c_void_p] * 3 + [C.c_int] * 3 + [C.c_void_p] * 2
+        for name in ("probe_route_topk", "probe_predict_topk", "probe_permute", "probe_grouped_ffn",
+                     "probe_combine"):
+            getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise ProbeError(rc, lib().probe_last_error_string().decode())
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _want(t, dtype, shape, name):
+    if t.dtype != dtype or tuple(t.shape) != tuple(shape) or not t.is_contiguous() or not t.is_cuda:
+        raise ValueError("%s: expected contiguous cuda %s %s, got %s %s" %
+                         (name, dtype, tuple(shape), t.dtype, tuple(t.shape)))
+    return t
+
+
+def _ws(workspace, nbytes, device):
+    if workspace is None:
+        workspace = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+    return workspace
+
+
+# --------------------------------------------------------------------- route / predict
+
+def route_topk_workspace_bytes(T, H, E, k):
+    return int(lib().probe_route_topk_workspace_bytes(T, H, E, k))
+
+
+predict_topk_workspace_bytes = route_topk_workspace_bytes
+
+
+def _route(fn, x, w_gate, bias, tokens_per_group, k, renormalize, want_probs, want_counts, out,
+           workspace, stream):
+    T, H = x.shape
+    E = w_gate.shape[0]
+    _want(x, torch.bfloat16, (T, H), "x")
+    _want(w_gate, torch.float32, (E, H), "w_gate")
+    G = 1
+    if bias is not None:
+        if bias.dim() == 1:
+            bias = bias.view(1, E)
+        G = bias.shape[0]
+        _want(bias, torch.float32, (G, E), "bias")
+    tpg = int(tokens_per_group) if tokens_per_group else max(T, 1)
+    out = dict(out) if out else {}
+    dev = x.device
+    if "idx" not in out:
+        out["idx"] = torch.empty((T, k), dtype=torch.int32, device=dev)
+    if "w" not in out:
+        out["w"] = torch.empty((T, k), dtype=torch.float32, device=dev)
+    if want_probs and "probs" not in out:
+        out["probs"] = torch.empty((T, E), dtype=torch.float32, device=dev)
+    if want_counts and "counts" not in out:
+        out["counts"] = torch.empty((E,), dtype=torch.int32, device=dev)
+    _want(out["idx"], torch.int32, (T, k), "idx")
+    _want(out["w"], torch.float32, (T, k), "w")
+    probs = out.get("probs") if want_probs else None
+    counts = out.get("counts") if want_counts else None
+    nbytes = route_topk_workspace_bytes(T, H, E, k)
+    workspace = _ws(workspace, nbytes, dev)
+    rc = fn(_ptr(x), _ptr(w_gate), _ptr(bias), G, tpg, T, H, E, k, int(bool(renormalize)),
+            _ptr(out["idx"]), _ptr(out["w"]), _ptr(probs), _ptr(counts), _ptr(workspace),
+            workspace.numel(), _stream(stream))
+    _check(rc)
+    return out
+
+
+def route_topk(x, w_gate, bias=None, tokens_per_group=None, k=2, renormalize=True, *,
+               want_probs=False, want_counts=True, out=None, workspace=None, stream=None):
+    """probe_route_topk: returns dict(idx int32 [T,k], w fp32 [T,k], probs?, counts?)."""
+    return _route(lib().probe_route_topk, x, w_gate, bias, tokens_per_group, k, renormalize,
+                  want_probs, want_counts, out, workspace, stream)
+
+
+def predict_topk(h_prev, w_gate_next, bias_next=None, tokens_per_group=None, k=2,
+                 renormalize=True, *, want_probs=False, want_counts=True, out=None, workspace=None,
+                 stream=None):
+    """probe_predict_topk: lookahead predictor; ``counts`` is the predicted workload n-hat."""
+    return _route(lib().probe_predict_topk, h_prev, w_gate_next, bias_next, tokens_per_group, k,
+                  renormalize, want_probs, want_counts, out, workspace, stream)
+
+
+# ------------------------------------------------------------------------------ permute
+
+class Plan:
+    """Device copy of a balance plan (rep_off [E+1], rep_slot [R], rep_weight [R], S)."""
+
+    def __init__(self, rep_off, rep_slot, rep_weight, num_slots, device="cuda"):
+        def dev(a):
+            return torch.as_tensor(a, dtype=torch.int32).contiguous().to(device)
+        self.rep_off, self.rep_slot, self.rep_weight = dev(rep_off), dev(rep_slot), dev(rep_weight)
+        self.num_slots = int(num_slots)
+        self.num_experts = self.rep_off.numel() - 1
+        self.c = _Plan(self.rep_off.data_ptr(), self.rep_slot.data_ptr(), self.rep_weight.data_ptr(),
+                       self.num_slots)
+
+
+def permute_workspace_bytes(T, E, k, S):
+    return int(lib().probe_permute_workspace_bytes(T, E, k, S))
+
+
+def permute(topk_idx, plan: Plan, x, *, out=None, workspace=None, stream=None):
+    """probe_permute: returns dict(slot_counts, slot_offsets, row_pair, pair_row, xp, n_local)."""
+    T, k = topk_idx.shape
+    H = x.shape[1]
+    E, S = plan.num_experts, plan.num_slots
+    _want(topk_idx, torch.int32, (T, k), "topk_idx")
+    _want(x, torch.bfloat16, (T, H), "x")
+    dev = x.device
+    out = dict(out) if out else {}
+    N = T * k
+    spec = dict(slot_counts=((S,), torch.int32), slot_offsets=((S + 1,), torch.int32),
+                row_pair=((N,), torch.int32), pair_row=((T, k), torch.int32),
+                xp=((N, H), torch.bfloat16), n_local=((1,), torch.int32))
+    for name, (shape, dt) in spec.items():
+        if name not in out:
+            out[name] = torch.empty(shape, dtype=dt, device=dev)
+        _want(out[name], dt, shape, name)
+    workspace = _ws(workspace, permute_workspace_bytes(T, E, k, S), dev)
+    rc = lib().probe_permute(_ptr(topk_idx), C.byref(plan.c), _ptr(x), T, H, E, k,
+                             _ptr(out["slot_counts"]), _ptr(out["slot_offsets"]),
+                             _ptr(out["row_pair"]), _ptr(out["pair_row"]), _ptr(out["xp"]),
+                             _ptr(out["n_local"]), _ptr(workspace), workspace.numel(),
+                             _stream(stream))
+    _check(rc)
+    return out
+
+
+# -------------------------------------------------------------------------- grouped FFN
+
+class WeightTable:
+    """Device arrays of per-slot weight pointers; keeps the weight tensors alive."""
+
+    def __init__(self, w13_list, w2_list):
+        assert len(w13_list) == len(w2_list) and len(w13_list) >= 1
+        self.S = len(w13_list)
+        self.F, self.H = w2_list[0].shape[1], w2_list[0].shape[0]
+        for a, b in zip(w13_list, w2_list):
+            _want(a, torch.bfloat16, (2 * self.F, self.H), "w13")
+            _want(b, torch.bfloat16, (self.H, self.F), "w2")
+        self.w13, self.w2 = list(w13_list), list(w2_list)
+        dev = w13_list[0].device
+        self.w13_ptrs = torch.tensor([t.data_ptr() for t in w13_list], dtype=torch.int64).to(dev)
+        self.w2_ptrs = torch.tensor([t.data_ptr() for t in w2_list], dtype=torch.int64).to(dev)
+
+
+def grouped_ffn_workspace_bytes(S, H, F, max_rows):
+    return int(lib().probe_grouped_ffn_workspace_bytes(S, H, F, max_rows))
+
+
+def grouped_ffn(xp, slot_offsets, weights: WeightTable, *, out=None, workspace=None, stream=None):
+    """probe_grouped_ffn: y bf16 [max_rows,H]; rows >= slot_offsets[-1] are left untouched."""
+    max_rows, H = xp.shape
+    S, F = weights.S, weights.F
+    _want(xp, torch.bfloat16, (max_rows, H), "xp")
+    _want(slot_offsets, torch.int32, (S + 1,), "slot_offsets")
+    assert H == weights.H
+    if out is None:
+        out = torch.empty((max_rows, H), dtype=torch.bfloat16, device=xp.device)
+    _want(out, torch.bfloat16, (max_rows, H), "y")
+    workspace = _ws(workspace, grouped_ffn_workspace_bytes(S, H, F, max_rows), xp.device)
+    rc = lib().probe_grouped_ffn(_ptr(xp), _ptr(slot_offsets), _ptr(weights.w13_ptrs),
+                                 _ptr(weights.w2_ptrs), S, H, F, max_rows, _ptr(out),
+                                 _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(rc)
+    return out
+
+
+# ------------------------------------------------------------------------------ combine
+
+def combine(y, pair_row, topk_w, *, out=None, stream=None):
+    """probe_combine: out bf16 [T,H]."""
+    T, k = pair_row.shape
+    H = y.shape[1]
+    _want(y, torch.bfloat16, (y.shape[0], H), "y")
+    _want(pair_row, torch.int32, (T, k), "pair_row")
+    _want(topk_w, torch.float32, (T, k), "topk_w")
+    if out is None:
+        out = torch.empty((T, H), dtype=torch.bfloat16, device=y.device)
+    _want(out, torch.bfloat16, (T, H), "out")
+    rc = lib().probe_combine(_ptr(y), _ptr(pair_row), _ptr(topk_w), T, H, k, _ptr(out),
+                             _stream(stream))
+    _check(rc)
+    return out
+
+
+# names of the C entry points, for callers that prefer them
+probe_route_topk = route_topk
+probe_predict_topk = predict_topk
+probe_permute = permute
+probe_grouped_ffn = grouped_ffn
+probe_combine = combine
+
+
+def version() -> str:
+    return lib().probe_version().decode()

@@ -1,0 +1,77 @@
+"""GPU parity: libprobe (HIP, through the C ABI) against the CPU oracle, stage by stage.
+
+Bars: integer outputs bit-exact (top-k indices wherever the oracle's order is unambiguous at
+1e-4 in the logits, otherwise a valid top-k within that margin); gate probabilities and
+weights within 1e-5 absolute; bf16 outputs within 2e-2 of the fp64 oracle in the metric
+max |g-o| / (|o| + rms(o))."""
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2602_00509_amd import workload as wl
+
+pytestmark = pytest.mark.gpu
+
+@pytest.fixture(scope="module")
+def probe():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    from paper_2602_00509_amd import probe as p
+    p.lib()                     # raises if libprobe.so is missing: there is no fallback
+    return p
+
+
+@pytest.fixture(scope="module")
+def G():
+    import gpu_util
+    return gpu_util
+
+
+REPORT = []
+
+
+def _flush_report():
+    os.makedirs("gpurun_out", exist_ok=True)
+    with open("gpurun_out/parity_report.json", "w") as f:
+        json.dump(REPORT, f, indent=1, default=str)
+
+
+SMALL = [
+    # ragged tails everywhere: T not a multiple of 64/128, odd expert counts, several tiles
+    dict(T=96, H=128, E=16, k=4, F=192, E_loc=4, n_rep=2, ep=4, chunk=32),
+    dict(T=333, H=256, E=10, k=3, F=320, E_loc=10, n_rep=2, ep=1, chunk=0),
+    dict(T=1, H=64, E=8, k=1, F=64, E_loc=8, n_rep=1, ep=1, chunk=0),
+    dict(T=700, H=192, E=200, k=8, F=128, E_loc=50, n_rep=3, ep=4, chunk=128),
+    dict(T=1100, H=64, E=3, k=2, F=64, E_loc=3, n_rep=1, ep=1, chunk=0),     # slots of > 128 rows
+    dict(T=257, H=512, E=256, k=8, F=448, E_loc=32, n_rep=4, ep=8, chunk=0),
+]
+
+
+@pytest.mark.parametrize("i", range(len(SMALL)))
+@pytest.mark.parametrize("renorm", [True, False])
+def test_small_layers(oracle, probe, G, i, renorm):
+    cfg = wl.small_config(cid=90 + i, **SMALL[i])
+    print("case small", i, SMALL[i], "renorm", renorm, flush=True)
+    G.run_layer_parity(oracle, probe, cfg, batch=0, renormalize=renorm, seed=i, report=REPORT)
+    _flush_report()
+
+
+@pytest.mark.parametrize("cid,batch", [(1, 0), (1, 1), (4, 0), (4, 3)])
+def test_full_configs_every_element(oracle, probe, G, cid, batch):
+    """Configurations small enough for the oracle to compute every output element."""
+    print("case full", cid, batch, flush=True)
+    G.run_layer_parity(oracle, probe, wl.CONFIGS[cid], batch=batch, seed=cid, report=REPORT)
+    _flush_report()
+
+
+@pytest.mark.parametrize("cid,batch", [(2, 0), (3, 0), (3, 5), (5, 0)])
+def test_full_configs_sampled(oracle, probe, G, cid, batch):
+    """Full benchmark sizes: integer stages checked completely, floating-point stages on
+    sampled tokens / rows that the oracle computes one by one."""
+    print("case sampled", cid, batch, flush=True)
+    G.run_layer_parity(oracle, probe, wl.CONFIGS[cid], batch=batch, route_sample=512, ffn_sample=48,
+                       seed=cid, report=REPORT)
+    _flush_report()
