@@ -1,0 +1,230 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE-layer hot path on one MI355X.
+
+One "step" is one pass of the whole path over one batch of synthetic tokens:
+predict_topk (next layer's cloned gate) -> route_topk -> permute -> grouped_ffn -> combine,
+all through the C ABI of libprobe.so on one stream, inputs resident in HBM, every buffer
+pre-allocated.  The default workload is the DeepSeek-V3-shaped shard (configuration 3 of
+the benchmark spec, the one the target is quoted on); successive steps rotate over 8 batches whose
+hot expert set moves, so no step re-reads the previous step's activations from cache.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--config", type=int, default=3, help="BASELINE.json configuration (1-5)")
+    ap.add_argument("--batches", type=int, default=0, help="distinct batches to rotate over (0 = config default)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build is a one-GPU hot path (no collectives); run with --gpus 1")
+        sys.exit(2)
+
+    import torch
+    from paper_2602_00509_amd import probe, workload as wl
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        sys.exit(3)
+    probe.lib()                                   # fail loudly if the HIP library is missing
+    cfg = wl.CONFIGS[args.config]
+    T, H, E, k, F, S = cfg.T, cfg.H, cfg.E, cfg.k, cfg.F, cfg.S
+    nb = args.batches or min(cfg.n_batches, 8)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    threads = min(16, os.cpu_count() or 8)
+
+    def dev_bf16(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(dev).view(torch.bfloat16)
+
+    # ------------------------------------------------------------------ inputs
+    t0 = time.time()
+    wg = wl.gate_weights(cfg, 0)
+    wg_next = wl.gate_weights(cfg, 1)
+    d_wg, d_wg_next = torch.from_numpy(wg).to(dev), torch.from_numpy(wg_next).to(dev)
+    tpg = wl.tokens_per_group(cfg)
+    xs, d_xs, d_bias, d_bias_next, biases = [], [], [], [], []
+    for b in range(nb):
+        x = wl.activations(cfg, b)
+        xs.append(x)
+        d_xs.append(dev_bf16(x))
+        biases.append(wl.zipf_bias(cfg, b, 0))
+        d_bias.append(torch.from_numpy(biases[-1]).to(dev))
+        d_bias_next.append(torch.from_numpy(wl.zipf_bias(cfg, b, 1)).to(dev))
+    log("inputs: %d batches of %dx%d in %.1fs" % (nb, T, H, time.time() - t0))
+
+    # pre-allocated outputs and workspaces (one set, reused by every step)
+    N = T * k
+    r_out = dict(idx=torch.empty((T, k), dtype=torch.int32, device=dev),
+                 w=torch.empty((T, k), dtype=torch.float32, device=dev),
+                 counts=torch.empty((E,), dtype=torch.int32, device=dev))
+    p_out_pred = dict(idx=torch.empty((T, k), dtype=torch.int32, device=dev),
+                      w=torch.empty((T, k), dtype=torch.float32, device=dev),
+                      counts=torch.empty((E,), dtype=torch.int32, device=dev))
+    ws_route = torch.empty(probe.route_topk_workspace_bytes(T, H, E, k), dtype=torch.uint8, device=dev)
+    ws_perm = torch.empty(max(256, probe.permute_workspace_bytes(T, E, k, S)), dtype=torch.uint8, device=dev)
+    ws_ffn = torch.empty(probe.grouped_ffn_workspace_bytes(S, H, F, N), dtype=torch.uint8, device=dev)
+    perm_out = dict(slot_counts=torch.empty((S,), dtype=torch.int32, device=dev),
+                    slot_offsets=torch.empty((S + 1,), dtype=torch.int32, device=dev),
+                    row_pair=torch.empty((N,), dtype=torch.int32, device=dev),
+                    pair_row=torch.empty((T, k), dtype=torch.int32, device=dev),
+                    xp=torch.empty((N, H), dtype=torch.bfloat16, device=dev),
+                    n_local=torch.empty((1,), dtype=torch.int32, device=dev))
+    y = torch.empty((N, H), dtype=torch.bfloat16, device=dev)
+    out = torch.empty((T, H), dtype=torch.bfloat16, device=dev)
+
+    # plans: the host recipe of the workload, from each batch's routed counts (set-up, untimed)
+    plans, d_plans, n_locals, slot_experts, active_slots = [], [], [], [], []
+    for b in range(nb):
+        probe.route_topk(d_xs[b], d_wg, d_bias[b], tpg, k, True, out=r_out, workspace=ws_route)
+        counts = r_out["counts"].cpu().numpy()
+        plan = wl.build_plan(cfg, counts)
+        plans.append(plan)
+        d_plans.append(probe.Plan(plan["rep_off"], plan["rep_slot"], plan["rep_weight"], plan["num_slots"], dev))
+        slot_experts.append(plan["slot_expert"])
+    # expert weights: one buffer per (expert) used by any batch; a slot table per batch
+    t0 = time.time()
+    need = sorted({int(e) for se in slot_experts for e in se})
+    host_w = dict(zip(need, wl.expert_weights_many(cfg, need, threads=threads)))
+    dev_w = {e: (dev_bf16(host_w[e][0]), dev_bf16(host_w[e][1])) for e in need}
+    tables = [probe.WeightTable([dev_w[int(e)][0] for e in se], [dev_w[int(e)][1] for e in se])
+              for se in slot_experts]
+    log("expert weights: %d experts (%.2f GB) in %.1fs" %
+        (len(need), len(need) * 3 * H * F * 2 / 1e9, time.time() - t0))
+
+    def step(b, ev=None):
+        def mark(i):
+            if ev is not None:
+                ev[i].record()
+        mark(0)
+        probe.predict_topk(d_xs[b], d_wg_next, d_bias_next[b], tpg, k, True, out=p_out_pred, workspace=ws_route)
+        mark(1)
+        probe.route_topk(d_xs[b], d_wg, d_bias[b], tpg, k, True, out=r_out, workspace=ws_route)
+        mark(2)
+        probe.permute(r_out["idx"], d_plans[b], d_xs[b], out=perm_out, workspace=ws_perm)
+        mark(3)
+        probe.grouped_ffn(perm_out["xp"], perm_out["slot_offsets"], tables[b], out=y, workspace=ws_ffn)
+        mark(4)
+        probe.combine(y, perm_out["pair_row"], r_out["w"], out=out)
+        mark(5)
+
+    for b in range(nb):                           # rows per batch (set-up; also first warm-up)
+        step(b)
+        n_locals.append(int(perm_out["n_local"].item()))
+        active_slots.append(int((perm_out["slot_counts"] > 0).sum().item()))
+    for i in range(args.warmup):
+        step(i % nb)
+    torch.cuda.synchronize()
+
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for i in range(args.steps):
+        step(i % nb, events[i])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+
+    names = ["predict", "route", "permute", "ffn", "combine"]
+    stage_ms = {n: [] for n in names}
+    for i in range(args.steps):
+        for j, n in enumerate(names):
+            stage_ms[n].append(events[i][j].elapsed_time(events[i][j + 1]))
+    mean_ms = {n: float(np.mean(v)) for n, v in stage_ms.items()}
+    ms_per_step = elapsed * 1e3 / args.steps
+    nl_steps = [n_locals[i % nb] for i in range(args.steps)]
+    nl_mean = float(np.mean(nl_steps))
+
+    # algorithmic work per step (mean over the batches the timed steps used)
+    ffn_flops = 6.0 * nl_mean * H * F
+    ffn_tflops = ffn_flops / (mean_ms["ffn"] * 1e-3) / 1e12
+    route_bytes = T * H * 2 + E * H * 4 + T * k * 8
+    perm_bytes = T * k * 4 + T * H * 2 + nl_mean * H * 2 + 16 * T * k
+    comb_bytes = nl_mean * H * 2 + T * H * 2 + T * k * 8
+    gbps = {"predict": route_bytes / mean_ms["predict"] / 1e6, "route": route_bytes / mean_ms["route"] / 1e6,
+            "permute": perm_bytes / mean_ms["permute"] / 1e6, "combine": comb_bytes / mean_ms["combine"] / 1e6}
+    act_mean = float(np.mean([active_slots[i % nb] for i in range(args.steps)]))
+    ffn_bytes = act_mean * 3 * H * F * 2 + 2 * nl_mean * H * 2   # weights of non-empty slots once + xp + y
+
+    result = {
+        "metric": "moe_layer_tokens_per_s",
+        "value": T * args.steps / elapsed,
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "cfg%d %s: T=%d H=%d E=%d top-%d F=%d, %d native + %d replica slots, Zipf s=%.1f, "
+                               "%d rotating batches" % (cfg.cid, cfg.name, T, H, E, k, F, cfg.E_loc, cfg.n_rep,
+                                                        cfg.zipf_s, nb),
+                   "step": "predict_topk + route_topk + permute + grouped_ffn + combine",
+                   "rows_per_step_mean": nl_mean, "active_slots_mean": act_mean},
+        "stage_ms": mean_ms,
+        "stage_ms_min": {n: float(np.min(v)) for n, v in stage_ms.items()},
+        "main_track_tokens_per_s": T / ((mean_ms["route"] + mean_ms["permute"] + mean_ms["ffn"] + mean_ms["combine"]) * 1e-3),
+        "ffn_tflops": ffn_tflops,
+        "ffn_frac_bf16_mfma_peak": ffn_tflops / PEAK_BF16_TFLOPS,
+        "ffn_weight_stream_gbps": ffn_bytes / mean_ms["ffn"] / 1e6,
+        "stage_hbm_gbps": gbps,
+        "stage_frac_hbm_peak": {n: v / PEAK_HBM_GBPS for n, v in gbps.items()},
+        "roofline": {"kernel": "probe_grouped_ffn (ffn_gemm1_kernel + ffn_gemm2_kernel)", "bound": "mfma",
+                     "achieved": ffn_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": ffn_tflops / PEAK_BF16_TFLOPS, "traffic": None},
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, xs[0], wg, biases[0], tpg, plans[0], host_w, slot_experts[0],
+                                              args.cpu_sample_tokens)
+    print(json.dumps(result), flush=True)
+
+
+def cpu_baseline(cfg, x, wg, bias, tpg, plan, host_w, slot_expert, sample_tokens):
+    """The CPU oracle, as it stands, on the first tokens of batch 0 (whole layer per token)."""
+    import oracle
+    oracle.build()
+    chunk = 64
+    budget_s = 12.0 if not sample_tokens else 1e9
+    limit = min(sample_tokens or cfg.T, cfg.T)
+    w13 = [host_w[int(e)][0] for e in slot_expert]
+    w2 = [host_w[int(e)][1] for e in slot_expert]
+    done, rows = 0, 0
+    t0 = time.perf_counter()
+    while done < limit and time.perf_counter() - t0 < budget_s:
+        t1 = min(limit, done + chunk)
+        g = np.minimum(np.arange(done, t1) // tpg, bias.shape[0] - 1)
+        res = oracle.moe_layer(x[done:t1], wg, np.ascontiguousarray(bias[g]), 1, cfg.k, True, plan, w13, w2)
+        rows += res["permute"]["n_local"]
+        done = t1
+        chunk = min(chunk * 2, 1024)
+    dt = time.perf_counter() - t0
+    return {"value": done / dt, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "first %d tokens of batch 0 through the whole oracle layer in chunks "
+                      "(route, permute, FFN of the %d local rows, combine), %.1f s" % (done, rows, dt)}
+
+
+if __name__ == "__main__":
+    main()
