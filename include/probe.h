@@ -85,7 +85,7 @@ const char* probe_version(void);
  *
  * Arithmetic: x is bf16 exactly, w_gate is used at full fp32 precision (three bf16 planes
  * on the matrix cores), accumulation in fp32.
- * Limits: 1 <= k <= 8, k <= E <= 256, H % 32 == 0, T >= 0 (T = 0 writes only zero counts).
+ * Limits: 1 <= k <= 8, k <= E <= 256, H % 8 == 0, T >= 0 (T = 0 writes only zero counts).
  */
 size_t probe_route_topk_workspace_bytes(int T, int H, int E, int k);
 
@@ -165,7 +165,7 @@ int probe_permute(const int32_t* topk_idx, const probe_plan* plan, const void* x
  *
  * bf16 inputs, fp32 accumulation on the matrix cores, h rounded to bf16 between the two
  * GEMMs, bf16 output.  An empty slot does no work and its weights are not read.
- * Limits: H % 64 == 0, F % 64 == 0, 1 <= S <= 1024.
+ * Limits: H % 64 == 0, F % 64 == 0, 1 <= S <= 1024, one expert's w13 below 4 GiB.
  */
 size_t probe_grouped_ffn_workspace_bytes(int S, int H, int F, int max_rows);
 

@@ -1,25 +1,48 @@
 // probe_grouped_ffn: grouped SwiGLU expert FFN on the bf16 matrix cores.
 //
-//   0. schedule  turn slot_offsets into a table of 128-row tiles (slot, first row), on device
+//   0. schedule  turn slot_offsets into a table of row tiles (slot, first row, height), on device
 //   1. gemm1     h[r, f] = silu(xp[r] . W1[f]) * (xp[r] . W3[f])        (K = H)
 //   2. gemm2     y[r, n] = h[r] . W2[n]                                  (K = F)
 //
 // Both GEMMs are "NT": activations [rows, K] and weights [out, K] are K-contiguous, which is
-// exactly the 8-consecutive-k-per-lane operand layout of v_mfma_f32_32x32x16_bf16, so LDS
-// fragments are single 16-byte reads.  A workgroup (4 waves, 2x2) computes a 128x128 output
-// tile in steps of 64 k: global -> registers (prefetch of the next step) -> swizzled LDS ->
-// MFMA.  In gemm1 a workgroup's 128 weight rows are 64 gate rows plus the 64 matching up rows,
-// arranged so that each lane holds gate and up of the same output element and SwiGLU is
-// applied on the accumulators.  Ragged row counts are handled by clamping loads to the
-// slot's last row and masking stores; no padding of the row space is required.
+// the 8-consecutive-k-per-lane operand layout of v_mfma_f32_32x32x16_bf16, so an MFMA operand
+// is one 16-byte LDS read.
+//
+// One workgroup = 8 waves (2 x 4) computes a 256 x 256 output tile (128 x 256 for the ragged
+// remainder of a slot) in steps of 64 k:
+//   * global -> LDS goes through buffer_load ... lds (no register staging).  The per-lane
+//     offset is fixed for the whole K loop; the k position travels in a scalar offset.
+//   * two LDS stages of 64 KB.  Rows are 128 bytes; 16-byte chunk c of row r is stored at chunk
+//     position c ^ ((r >> 1) & 7), which makes sixteen consecutive rows reading the same
+//     logical chunk cover all 64 banks exactly once.
+//   * per k-step a wave runs four groups of MFMAs; the fragments of group g+1 are read from LDS
+//     while group g executes.  The workgroup barrier sits before the last group, whose MFMAs
+//     are interleaved one-to-one with the DMA instructions that prefetch tile k+2 into the
+//     stage that was just vacated, and overlap the first fragment reads of tile k+1.
+//
+// In gemm1 a workgroup's 256 weight rows are 128 gate rows plus the 128 matching up rows,
+// arranged so that each lane holds gate and up of the same output element; SwiGLU is applied
+// on the accumulators.  Ragged row counts are handled by clamping the row a lane loads to
+// the slot's last row and masking stores; the row space is never padded.
+#include <mutex>
+#include <type_traits>
+
 #include "common.hpp"
 
 namespace probe {
 
-constexpr int FBM = 128, FBN = 128, FBK = 64;
+constexpr int FBN = 256, FBK = 64;
+constexpr int kStageUnits = (256 + 256) * 8;  // 16-byte units per LDS stage (sized for the tall tile)
+constexpr int kFfnLdsBytes = 2 * kStageUnits * 16;
+
+#define PROBE_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 
 // ---- 0. schedule ----------------------------------------------------------------------
-// table[0] = number of tiles; table[1 + 2*i] = slot, table[2 + 2*i] = first row of tile i.
+// table[0] = number of tiles; tile i: table[1+3i] = slot, table[2+3i] = first row,
+// table[3+3i] = tile height (256 or 128).  A slot of M rows gets floor(M/256) tall tiles and,
+// for the remainder r, one more tall tile if r > 128, one short tile if 0 < r <= 128.
+__device__ __forceinline__ int slot_tiles(int m) { return m / 256 + ((m % 256) ? 1 : 0); }
+
 __global__ __launch_bounds__(256) void ffn_schedule_kernel(const int32_t* __restrict__ slot_offsets,
                                                            int S, int max_tiles,
                                                            int32_t* __restrict__ table) {
@@ -32,7 +55,7 @@ __global__ __launch_bounds__(256) void ffn_schedule_kernel(const int32_t* __rest
     int s = tid * 4 + i;
     int m = 0;
     if (s < S) m = max(slot_offsets[s + 1] - slot_offsets[s], 0);
-    v[i] = (m + FBM - 1) / FBM;
+    v[i] = slot_tiles(m);
     local += v[i];
   }
   int incl = local;
@@ -61,165 +84,260 @@ __global__ __launch_bounds__(256) void ffn_schedule_kernel(const int32_t* __rest
       int mid = (lo + hi) >> 1;
       if (tile_start[mid] <= t) lo = mid; else hi = mid;
     }
-    table[1 + 2 * t] = lo;
-    table[2 + 2 * t] = slot_offsets[lo] + (t - tile_start[lo]) * FBM;
+    int first = slot_offsets[lo], m = slot_offsets[lo + 1] - first;
+    int local_t = t - tile_start[lo];
+    int row0 = first + local_t * 256;
+    int left = m - local_t * 256;
+    table[1 + 3 * t] = lo;
+    table[2 + 3 * t] = row0;
+    table[3 + 3 * t] = left > 128 ? 256 : 128;
   }
 }
 
 // ---- shared main loop -----------------------------------------------------------------
-// acc += A_tile[128, K] * B_tile[128, K]^T.  a_row(i) / b_row(j) give the K-contiguous global
-// row behind tile row i / j (already clamped to valid memory).  Wave (wm, wn) accumulates the
-// 64x64 block at tile rows 64*wm and tile columns 64*wn as 2x2 MFMA tiles.
-template <typename AF, typename BF>
-__device__ __forceinline__ void mainloop_128x128(AF a_row, BF b_row, int K, u32x4* sA, u32x4* sB,
-                                                 f32x16 (&acc)[2][2]) {
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  const int wm = wv >> 1, wn = wv & 1;
-  const bf16_t* pa[4];
-  const bf16_t* pb[4];
-  int soff[4];
+// acc += A_tile[64*MI, K] * B_tile[256, K]^T for the calling wave's 32*MI x 64 block.
+// rA / rB are buffer descriptors of the tile's first A row / of the weight matrix; voff[j] is
+// this lane's byte offset for DMA instruction j (AW instructions for A, then 4 for B).
+template <int MI>
+__device__ __forceinline__ void gemm_mainloop(__amdgpu_buffer_rsrc_t rA, __amdgpu_buffer_rsrc_t rB,
+                                              const int (&voff)[MI + 4], int K, u32x4* smem, int wv,
+                                              int lane, f32x16 (&acc)[MI][2]) {
+  constexpr int NI = 2, WN = 4, AW = MI, BW = 4, LPW = AW + BW, BM = 64 * MI;
+  const int wm = wv / WN, wn = wv % WN;
+
+  auto issue_one = [&](int st, int j, int kbytes) {
+    if (j < AW)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rA, PROBE_LDS_PTR(smem + st * kStageUnits + (wv * AW + j) * 64), 16,
+                                               voff[j], kbytes, 0, 0);
+    else
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(
+          rB, PROBE_LDS_PTR(smem + st * kStageUnits + BM * 8 + (wv * BW + (j - AW)) * 64), 16, voff[j], kbytes, 0, 0);
+  };
+  int offA[MI], offB[NI];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    int idx = tid + 256 * j;
-    int row = idx >> 3, c = idx & 7;
-    pa[j] = a_row(row) + c * 8;
-    pb[j] = b_row(row) + c * 8;
-    soff[j] = lds_chunk_off(row, c);
+  for (int i = 0; i < MI; ++i) offA[i] = (32 * MI * wm + 32 * i + (lane & 31)) * 8;
+#pragma unroll
+  for (int j = 0; j < NI; ++j) offB[j] = BM * 8 + (64 * wn + 32 * j + (lane & 31)) * 8;
+  const int swz = ((lane & 31) >> 1) & 7;  // (row >> 1) & 7: every 32-row block starts at a multiple of 32
+  auto read_frags = [&](int st, int kk, u32x4(&a)[MI], u32x4(&b)[NI]) {
+    const u32x4* sbase = smem + st * kStageUnits;
+    const int pc = (2 * kk + (lane >> 5)) ^ swz;
+#pragma unroll
+    for (int i = 0; i < MI; ++i) a[i] = sbase[offA[i] + pc];
+#pragma unroll
+    for (int j = 0; j < NI; ++j) b[j] = sbase[offB[j] + pc];
+  };
+  auto mma = [&](u32x4(&a)[MI], u32x4(&b)[NI]) {
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int j = 0; j < NI; ++j) acc[i][j] = mfma_32x32x16(a[i], b[j], acc[i][j]);
+  };
+
+  const int KT = K / FBK;
+  u32x4 a0[MI], b0[NI], a1[MI], b1[NI];
+#pragma unroll
+  for (int j = 0; j < LPW; ++j) issue_one(0, j, 0);
+  __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  if (KT > 1) {
+#pragma unroll
+    for (int j = 0; j < LPW; ++j) issue_one(1, j, FBK * 2);
   }
-  u32x4 ra[4], rb[4];
+  read_frags(0, 0, a0, b0);
+  // One k-step.  DMA: prefetch tile kt+2 into the stage being vacated.  NEXT: a tile kt+1 exists.
+  auto k_step = [&](int kt, auto dma_c, auto next_c) {
+    constexpr bool DMA = decltype(dma_c)::value, NEXT = decltype(next_c)::value;
+    const int cur = kt & 1;
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): a0/b0 have arrived
+    read_frags(cur, 1, a1, b1);
+    __builtin_amdgcn_sched_barrier(0);
+    mma(a0, b0);
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(0xC07F);
+    read_frags(cur, 2, a0, b0);
+    __builtin_amdgcn_sched_barrier(0);
+    mma(a1, b1);
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(0xC07F);
+    read_frags(cur, 3, a1, b1);
+    __builtin_amdgcn_sched_barrier(0);
+    mma(a0, b0);
+    __builtin_amdgcn_sched_barrier(0);
+    // every read of stage cur is issued: wait for them and for this wave's share of tile kt+1
+    __builtin_amdgcn_s_waitcnt(0x0070);
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if constexpr (NEXT) read_frags(cur ^ 1, 0, a0, b0);
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (DMA) {
+      const int kbytes = (kt + 2) * FBK * 2;
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    ra[j] = *reinterpret_cast<const u32x4*>(pa[j]);
-    rb[j] = *reinterpret_cast<const u32x4*>(pb[j]);
-  }
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    sA[soff[j]] = ra[j];
-    sB[soff[j]] = rb[j];
-  }
-  __syncthreads();
-  for (int k0 = 0; k0 < K; k0 += FBK) {
-    const bool more = k0 + FBK < K;
-    if (more) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        ra[j] = *reinterpret_cast<const u32x4*>(pa[j] + k0 + FBK);
-        rb[j] = *reinterpret_cast<const u32x4*>(pb[j] + k0 + FBK);
+      for (int t = 0; t < MI * NI; ++t) {
+        acc[t / NI][t % NI] = mfma_32x32x16(a1[t / NI], b1[t % NI], acc[t / NI][t % NI]);
+        if (t < LPW) issue_one(cur, t, kbytes);
       }
-    }
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      const int c = 2 * kk + (lane >> 5);
-      u32x4 a[2], b[2];
+      for (int t = MI * NI; t < LPW; ++t) issue_one(cur, t, kbytes);
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        a[i] = sA[lds_chunk_off(64 * wm + 32 * i + (lane & 31), c)];
-        b[i] = sB[lds_chunk_off(64 * wn + 32 * i + (lane & 31), c)];
+      for (int t = 0; t < MI * NI; ++t) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // one VMEM read
       }
-#pragma unroll
-      for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = mfma_32x32x16(a[mi], b[ni], acc[mi][ni]);
+    } else {
+      mma(a1, b1);
     }
-    __syncthreads();
-    if (more) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        sA[soff[j]] = ra[j];
-        sB[soff[j]] = rb[j];
-      }
-      __syncthreads();
-    }
+  };
+  using T_ = std::integral_constant<bool, true>;
+  using F_ = std::integral_constant<bool, false>;
+  int kt = 0;
+  for (; kt + 2 < KT; ++kt) k_step(kt, T_{}, T_{});
+  if (kt + 1 < KT) {
+    k_step(kt, F_{}, T_{});
+    ++kt;
   }
+  k_step(kt, F_{}, F_{});
 }
 
-__device__ __forceinline__ void zero_acc(f32x16 (&acc)[2][2]) {
+template <int MI>
+__device__ __forceinline__ void zero_acc(f32x16 (&acc)[MI][2]) {
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 }
 
-// ---- 1. gemm1 + SwiGLU ----------------------------------------------------------------
-// grid.x = F/64 column blocks (64 gate + 64 up weight rows each), grid.y = tile capacity.
-__global__ __launch_bounds__(256, 2) void ffn_gemm1_kernel(const bf16_t* __restrict__ xp,
-                                                           const int32_t* __restrict__ table,
-                                                           const int32_t* __restrict__ slot_offsets,
-                                                           const void* const* __restrict__ w13_ptrs,
-                                                           int H, int F, bf16_t* __restrict__ hbuf) {
-  __shared__ u32x4 sA[FBM * 8];
-  __shared__ u32x4 sB[FBN * 8];
-  const int tile = blockIdx.y;
-  if (tile >= table[0]) return;
-  const int slot = table[1 + 2 * tile], row0 = table[2 + 2 * tile];
-  const int row_end = slot_offsets[slot + 1];
-  const int n0 = blockIdx.x * 64;
-  const bf16_t* w13 = static_cast<const bf16_t*>(w13_ptrs[slot]);
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  const int wm = wv >> 1, wn = wv & 1;
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, size_t bytes) {
+  unsigned n = bytes > 0xffffffffull ? 0xffffffffu : static_cast<unsigned>(bytes);
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, static_cast<int>(n), 0x00020000);
+}
 
-  f32x16 acc[2][2];
-  zero_acc(acc);
-  auto a_row = [&](int i) { return xp + static_cast<long>(min(row0 + i, row_end - 1)) * H; };
-  // tile column j: wave column block q = j/64; inside it 32 gate rows then the 32 up rows
-  auto b_row = [&](int j) {
-    int q = j >> 6, r = j & 63;
-    int wrow = (r < 32) ? (n0 + 32 * q + r) : (F + n0 + 32 * q + (r - 32));
-    return w13 + static_cast<long>(wrow) * H;
-  };
-  mainloop_128x128(a_row, b_row, H, sA, sB, acc);
+// Per-lane byte offsets of the DMA instructions of this wave: instruction j covers tile rows
+// (wv*CNT + j)*8 .. +8; lane l reads row +l/8, the chunk that belongs at LDS position l%8.
+template <int CNT, typename RowFn>
+__device__ __forceinline__ void dma_offsets(int wv, int lane, int row_bytes, RowFn row_of, int* out) {
+#pragma unroll
+  for (int j = 0; j < CNT; ++j) {
+    int row = (wv * CNT + j) * 8 + (lane >> 3);
+    int c = (lane & 7) ^ ((row >> 1) & 7);
+    out[j] = row_of(row) * row_bytes + c * 16;
+  }
+}
+
+// ---- 1. gemm1 + SwiGLU ----------------------------------------------------------------
+template <int MI>
+__device__ __forceinline__ void gemm1_tile(const bf16_t* __restrict__ xp, const bf16_t* __restrict__ w13,
+                                           int row0, int row_end, int n0, int H, int F,
+                                           bf16_t* __restrict__ hbuf, u32x4* smem) {
+  const int lane = threadIdx.x & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wv / 4, wn = wv % 4;
+  const int rows = row_end - row0;  // valid rows from row0 on (may exceed the tile height)
+  __amdgpu_buffer_rsrc_t rA = make_rsrc(xp + static_cast<size_t>(row0) * H, static_cast<size_t>(rows) * H * 2);
+  __amdgpu_buffer_rsrc_t rB = make_rsrc(w13, static_cast<size_t>(2) * F * H * 2);
+  int voff[MI + 4];
+  dma_offsets<MI>(wv, lane, H * 2, [&](int r) { return min(r, rows - 1); }, voff);
+  // weight tile row j: wave column block q = j / 64; inside it 32 gate rows, then the 32 up rows
+  dma_offsets<4>(wv, lane, H * 2,
+                 [&](int j) {
+                   int q = j >> 6, r = j & 63;
+                   int f = min(n0 + 32 * q + (r & 31), F - 1);  // columns past F are masked at the store
+                   return (r < 32) ? f : F + f;
+                 },
+                 voff + MI);
+  f32x16 acc[MI][2];
+  zero_acc<MI>(acc);
+  gemm_mainloop<MI>(rA, rB, voff, H, smem, wv, lane, acc);
 
   const int col = n0 + 32 * wn + mfma32_col(lane);
 #pragma unroll
-  for (int mi = 0; mi < 2; ++mi)
+  for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      int row = row0 + 64 * wm + 32 * mi + mfma32_row(r, lane);
-      if (row < row_end) {
+      int row = 32 * MI * wm + 32 * mi + mfma32_row(r, lane);
+      if (row < rows && col < F) {
         float g = acc[mi][0][r], u = acc[mi][1][r];
         float hval = g / (1.f + __expf(-g)) * u;
-        hbuf[static_cast<long>(row) * F + col] = f32_to_bf16(hval);
+        hbuf[static_cast<size_t>(row0 + row) * F + col] = f32_to_bf16(hval);
       }
     }
 }
 
-// ---- 2. gemm2 -------------------------------------------------------------------------
-// grid.x = ceil(H/128) column blocks, grid.y = tile capacity.
-__global__ __launch_bounds__(256, 2) void ffn_gemm2_kernel(const bf16_t* __restrict__ hbuf,
+// grid.x = ceil(F/128) column blocks (128 gate + 128 up weight rows each), grid.y = tile capacity.
+__global__ __launch_bounds__(512, 2) void ffn_gemm1_kernel(const bf16_t* __restrict__ xp,
                                                            const int32_t* __restrict__ table,
                                                            const int32_t* __restrict__ slot_offsets,
-                                                           const void* const* __restrict__ w2_ptrs,
-                                                           int H, int F, bf16_t* __restrict__ y) {
-  __shared__ u32x4 sA[FBM * 8];
-  __shared__ u32x4 sB[FBN * 8];
+                                                           const void* const* __restrict__ w13_ptrs,
+                                                           int H, int F, bf16_t* __restrict__ hbuf) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  extern __shared__ u32x4 smem[];
   const int tile = blockIdx.y;
   if (tile >= table[0]) return;
-  const int slot = table[1 + 2 * tile], row0 = table[2 + 2 * tile];
+  const int slot = table[1 + 3 * tile], row0 = table[2 + 3 * tile], height = table[3 + 3 * tile];
   const int row_end = slot_offsets[slot + 1];
-  const int n0 = blockIdx.x * FBN;
-  const bf16_t* w2 = static_cast<const bf16_t*>(w2_ptrs[slot]);
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  const int wm = wv >> 1, wn = wv & 1;
+  const int n0 = blockIdx.x * 128;
+  const bf16_t* w13 = static_cast<const bf16_t*>(w13_ptrs[slot]);
+  if (height > 128)
+    gemm1_tile<4>(xp, w13, row0, row_end, n0, H, F, hbuf, smem);
+  else
+    gemm1_tile<2>(xp, w13, row0, row_end, n0, H, F, hbuf, smem);
+#endif
+}
 
-  f32x16 acc[2][2];
-  zero_acc(acc);
-  auto a_row = [&](int i) { return hbuf + static_cast<long>(min(row0 + i, row_end - 1)) * F; };
-  auto b_row = [&](int j) { return w2 + static_cast<long>(min(n0 + j, H - 1)) * F; };
-  mainloop_128x128(a_row, b_row, F, sA, sB, acc);
+// ---- 2. gemm2 -------------------------------------------------------------------------
+template <int MI>
+__device__ __forceinline__ void gemm2_tile(const bf16_t* __restrict__ hbuf, const bf16_t* __restrict__ w2,
+                                           int row0, int row_end, int n0, int H, int F,
+                                           bf16_t* __restrict__ y, u32x4* smem) {
+  const int lane = threadIdx.x & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wv / 4, wn = wv % 4;
+  const int rows = row_end - row0;
+  __amdgpu_buffer_rsrc_t rA = make_rsrc(hbuf + static_cast<size_t>(row0) * F, static_cast<size_t>(rows) * F * 2);
+  __amdgpu_buffer_rsrc_t rB = make_rsrc(w2, static_cast<size_t>(H) * F * 2);
+  int voff[MI + 4];
+  dma_offsets<MI>(wv, lane, F * 2, [&](int r) { return min(r, rows - 1); }, voff);
+  dma_offsets<4>(wv, lane, F * 2, [&](int j) { return min(n0 + j, H - 1); }, voff + MI);
+  f32x16 acc[MI][2];
+  zero_acc<MI>(acc);
+  gemm_mainloop<MI>(rA, rB, voff, F, smem, wv, lane, acc);
 
 #pragma unroll
-  for (int mi = 0; mi < 2; ++mi)
+  for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
     for (int ni = 0; ni < 2; ++ni) {
       int col = n0 + 64 * wn + 32 * ni + mfma32_col(lane);
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        int row = row0 + 64 * wm + 32 * mi + mfma32_row(r, lane);
-        if (row < row_end && col < H) y[static_cast<long>(row) * H + col] = f32_to_bf16(acc[mi][ni][r]);
+        int row = 32 * MI * wm + 32 * mi + mfma32_row(r, lane);
+        if (row < rows && col < H) y[static_cast<size_t>(row0 + row) * H + col] = f32_to_bf16(acc[mi][ni][r]);
       }
     }
+}
+
+// grid.x = ceil(H/256) column blocks, grid.y = tile capacity.
+__global__ __launch_bounds__(512, 2) void ffn_gemm2_kernel(const bf16_t* __restrict__ hbuf,
+                                                           const int32_t* __restrict__ table,
+                                                           const int32_t* __restrict__ slot_offsets,
+                                                           const void* const* __restrict__ w2_ptrs,
+                                                           int H, int F, bf16_t* __restrict__ y) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  extern __shared__ u32x4 smem[];
+  const int tile = blockIdx.y;
+  if (tile >= table[0]) return;
+  const int slot = table[1 + 3 * tile], row0 = table[2 + 3 * tile], height = table[3 + 3 * tile];
+  const int row_end = slot_offsets[slot + 1];
+  const int n0 = blockIdx.x * FBN;
+  const bf16_t* w2 = static_cast<const bf16_t*>(w2_ptrs[slot]);
+  if (height > 128)
+    gemm2_tile<4>(hbuf, w2, row0, row_end, n0, H, F, y, smem);
+  else
+    gemm2_tile<2>(hbuf, w2, row0, row_end, n0, H, F, y, smem);
+#endif
 }
 
 struct FfnShape {
@@ -229,10 +347,28 @@ struct FfnShape {
 
 static FfnShape ffn_shape(int S, int F, int max_rows) {
   FfnShape s;
-  s.max_tiles = max_rows / FBM + S;
+  s.max_tiles = max_rows / 256 + S;
   s.h_bytes = align_up(static_cast<size_t>(max_rows > 0 ? max_rows : 1) * F * sizeof(bf16_t), 256);
-  s.table_bytes = align_up((1 + 2 * static_cast<size_t>(s.max_tiles)) * sizeof(int32_t), 256);
+  s.table_bytes = align_up((1 + 3 * static_cast<size_t>(s.max_tiles)) * sizeof(int32_t), 256);
   return s;
+}
+
+// The GEMM kernels use 128 KB of dynamic LDS, which has to be opted into once per process.
+static int ffn_prepare() {
+  static std::once_flag once;
+  static hipError_t err = hipSuccess;
+  std::call_once(once, [] {
+    err = hipFuncSetAttribute(reinterpret_cast<const void*>(ffn_gemm1_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, kFfnLdsBytes);
+    if (err == hipSuccess)
+      err = hipFuncSetAttribute(reinterpret_cast<const void*>(ffn_gemm2_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kFfnLdsBytes);
+  });
+  if (err != hipSuccess) {
+    set_error("probe_grouped_ffn: cannot reserve %d bytes of LDS: %s", kFfnLdsBytes, hipGetErrorString(err));
+    return PROBE_EHIP;
+  }
+  return PROBE_OK;
 }
 
 }  // namespace probe
@@ -254,6 +390,8 @@ extern "C" int probe_grouped_ffn(const void* xp_bf16, const int32_t* slot_offset
   PROBE_REQUIRE(S <= PROBE_MAX_SLOTS && H % 64 == 0 && F % 64 == 0, PROBE_EUNSUPPORTED,
                 "probe_grouped_ffn: needs S <= %d, H %% 64 == 0, F %% 64 == 0 (S=%d H=%d F=%d)",
                 PROBE_MAX_SLOTS, S, H, F);
+  PROBE_REQUIRE(static_cast<size_t>(2) * F * H * 2 <= 0xffffffffull, PROBE_EUNSUPPORTED,
+                "probe_grouped_ffn: one expert's w13 must stay below 4 GiB (H=%d F=%d)", H, F);
   if (max_rows == 0) return PROBE_OK;
   PROBE_REQUIRE(xp_bf16 && slot_offsets && w13_ptrs && w2_ptrs && y_bf16, PROBE_EINVAL,
                 "probe_grouped_ffn: null pointer");
@@ -265,13 +403,15 @@ extern "C" int probe_grouped_ffn(const void* xp_bf16, const int32_t* slot_offset
                 workspace_bytes, sh.h_bytes + sh.table_bytes);
   PROBE_REQUIRE(sh.max_tiles <= 65535, PROBE_EUNSUPPORTED, "probe_grouped_ffn: max_rows too large (%d)",
                 max_rows);
+  int rc = ffn_prepare();
+  if (rc != PROBE_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   bf16_t* hbuf = static_cast<bf16_t*>(workspace);
   int32_t* table = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + sh.h_bytes);
   hipLaunchKernelGGL(ffn_schedule_kernel, dim3(1), dim3(256), 0, st, slot_offsets, S, sh.max_tiles, table);
-  hipLaunchKernelGGL(ffn_gemm1_kernel, dim3(F / 64, sh.max_tiles), dim3(256), 0, st,
+  hipLaunchKernelGGL(ffn_gemm1_kernel, dim3((F + 127) / 128, sh.max_tiles), dim3(512), kFfnLdsBytes, st,
                      static_cast<const bf16_t*>(xp_bf16), table, slot_offsets, w13_ptrs, H, F, hbuf);
-  hipLaunchKernelGGL(ffn_gemm2_kernel, dim3((H + FBN - 1) / FBN, sh.max_tiles), dim3(256), 0, st, hbuf,
-                     table, slot_offsets, w2_ptrs, H, F, static_cast<bf16_t*>(y_bf16));
+  hipLaunchKernelGGL(ffn_gemm2_kernel, dim3((H + FBN - 1) / FBN, sh.max_tiles), dim3(512), kFfnLdsBytes, st,
+                     hbuf, table, slot_offsets, w2_ptrs, H, F, static_cast<bf16_t*>(y_bf16));
   return check_launch("probe_grouped_ffn");
 }
