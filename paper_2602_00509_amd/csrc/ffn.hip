@@ -8,11 +8,11 @@
 // the 8-consecutive-k-per-lane operand layout of v_mfma_f32_32x32x16_bf16, so an MFMA operand
 // is one 16-byte LDS read.
 //
-// One workgroup = 8 waves (2 x 4) computes a 256 x 256 output tile (128 x 256 for the ragged
-// remainder of a slot) in steps of 64 k:
+// One workgroup = 8 waves (2 x 4) computes a 256 x 256 output tile (128 x 256 or 64 x 256 for the
+// ragged remainder of a slot) in steps of 64 k:
 //   * global -> LDS goes through buffer_load ... lds (no register staging).  The per-lane
 //     offset is fixed for the whole K loop; the k position travels in a scalar offset.
-//   * two LDS stages of 64 KB.  Rows are 128 bytes; 16-byte chunk c of row r is stored at chunk
+//   * two LDS stages of 64 KB (three smaller ones for the short tiles).  Rows are 128 bytes; 16-byte chunk c of row r is stored at chunk
 //     position c ^ ((r >> 1) & 7), which makes sixteen consecutive rows reading the same
 //     logical chunk cover all 64 banks exactly once.
 //   * per k-step a wave runs four groups of MFMAs; the fragments of group g+1 are read from LDS
@@ -32,15 +32,17 @@
 namespace probe {
 
 constexpr int FBN = 256, FBK = 64;
-constexpr int kStageUnits = (256 + 256) * 8;  // 16-byte units per LDS stage (sized for the tall tile)
-constexpr int kFfnLdsBytes = 2 * kStageUnits * 16;
+// LDS: the tall tile (256 rows) runs two stages of 64 KB; the short tiles (128 / 64 rows) are bound
+// by load latency rather than by the matrix cores and run three stages of 48 / 40 KB, which
+// gives every DMA batch two k-steps to land.
+constexpr int kFfnLdsBytes = 3 * (128 + 256) * 128;  // 144 KB >= 2 * (256 + 256) * 128
 
 #define PROBE_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 
 // ---- 0. schedule ----------------------------------------------------------------------
 // table[0] = number of tiles; tile i: table[1+3i] = slot, table[2+3i] = first row,
-// table[3+3i] = tile height (256 or 128).  A slot of M rows gets floor(M/256) tall tiles and,
-// for the remainder r, one more tall tile if r > 128, one short tile if 0 < r <= 128.
+// table[3+3i] = tile height (256, 128 or 64).  A slot of M rows gets floor(M/256) tall tiles
+// and, for the remainder r, one more tile of the smallest height that holds r.
 __device__ __forceinline__ int slot_tiles(int m) { return m / 256 + ((m % 256) ? 1 : 0); }
 
 __global__ __launch_bounds__(256) void ffn_schedule_kernel(const int32_t* __restrict__ slot_offsets,
@@ -90,7 +92,7 @@ __global__ __launch_bounds__(256) void ffn_schedule_kernel(const int32_t* __rest
     int left = m - local_t * 256;
     table[1 + 3 * t] = lo;
     table[2 + 3 * t] = row0;
-    table[3 + 3 * t] = left > 128 ? 256 : 128;
+    table[3 + 3 * t] = left > 128 ? 256 : (left > 64 ? 128 : 64);
   }
 }
 
@@ -98,20 +100,33 @@ __global__ __launch_bounds__(256) void ffn_schedule_kernel(const int32_t* __rest
 // acc += A_tile[64*MI, K] * B_tile[256, K]^T for the calling wave's 32*MI x 64 block.
 // rA / rB are buffer descriptors of the tile's first A row / of the weight matrix; voff[j] is
 // this lane's byte offset for DMA instruction j (AW instructions for A, then 4 for B).
-template <int MI>
+// NST = LDS stages (2 or 3); a DMA batch is issued NST k-steps ahead of its use.
+template <int N>
+__device__ __forceinline__ void wait_vm_lgkm0() {  // s_waitcnt vmcnt(N) lgkmcnt(0), N < 16
+  __builtin_amdgcn_s_waitcnt(0x0070 | N);
+}
+
+template <int MI, int NST>
 __device__ __forceinline__ void gemm_mainloop(__amdgpu_buffer_rsrc_t rA, __amdgpu_buffer_rsrc_t rB,
-                                              const int (&voff)[MI + 4], int K, u32x4* smem, int wv,
-                                              int lane, f32x16 (&acc)[MI][2]) {
+                                              const int (&voff)[MI + 4], int K, u32x4* smem,
+                                              int wv, int lane, f32x16 (&acc)[MI][2]) {
   constexpr int NI = 2, WN = 4, AW = MI, BW = 4, LPW = AW + BW, BM = 64 * MI;
+  constexpr int kStage = (BM + 256) * 8;  // 16-byte units per stage
+  static_assert(NST == 2 || NST == 3, "two or three stages");
+  static_assert(NST * kStage * 16 <= kFfnLdsBytes, "LDS budget");
   const int wm = wv / WN, wn = wv % WN;
 
   auto issue_one = [&](int st, int j, int kbytes) {
     if (j < AW)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rA, PROBE_LDS_PTR(smem + st * kStageUnits + (wv * AW + j) * 64), 16,
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rA, PROBE_LDS_PTR(smem + st * kStage + (wv * AW + j) * 64), 16,
                                                voff[j], kbytes, 0, 0);
     else
       __builtin_amdgcn_raw_ptr_buffer_load_lds(
-          rB, PROBE_LDS_PTR(smem + st * kStageUnits + BM * 8 + (wv * BW + (j - AW)) * 64), 16, voff[j], kbytes, 0, 0);
+          rB, PROBE_LDS_PTR(smem + st * kStage + BM * 8 + (wv * BW + (j - AW)) * 64), 16, voff[j], kbytes, 0, 0);
+  };
+  auto issue_all = [&](int st, int kt) {
+#pragma unroll
+    for (int j = 0; j < LPW; ++j) issue_one(st, j, kt * FBK * 2);
   };
   int offA[MI], offB[NI];
 #pragma unroll
@@ -120,36 +135,48 @@ __device__ __forceinline__ void gemm_mainloop(__amdgpu_buffer_rsrc_t rA, __amdgp
   for (int j = 0; j < NI; ++j) offB[j] = BM * 8 + (64 * wn + 32 * j + (lane & 31)) * 8;
   const int swz = ((lane & 31) >> 1) & 7;  // (row >> 1) & 7: every 32-row block starts at a multiple of 32
   auto read_frags = [&](int st, int kk, u32x4(&a)[MI], u32x4(&b)[NI]) {
-    const u32x4* sbase = smem + st * kStageUnits;
+    const u32x4* sbase = smem + st * kStage;
     const int pc = (2 * kk + (lane >> 5)) ^ swz;
 #pragma unroll
     for (int i = 0; i < MI; ++i) a[i] = sbase[offA[i] + pc];
 #pragma unroll
     for (int j = 0; j < NI; ++j) b[j] = sbase[offB[j] + pc];
   };
+  // the weight fragment is the row operand: a lane's accumulator registers 4q..4q+3 are four
+  // consecutive output columns of one output row
   auto mma = [&](u32x4(&a)[MI], u32x4(&b)[NI]) {
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
-      for (int j = 0; j < NI; ++j) acc[i][j] = mfma_32x32x16(a[i], b[j], acc[i][j]);
+      for (int j = 0; j < NI; ++j) acc[i][j] = mfma_32x32x16(b[j], a[i], acc[i][j]);
   };
 
   const int KT = K / FBK;
   u32x4 a0[MI], b0[NI], a1[MI], b1[NI];
-#pragma unroll
-  for (int j = 0; j < LPW; ++j) issue_one(0, j, 0);
-  __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
+  // prologue: NST batches in flight, wait for the first
+  issue_all(0, 0);
+  if (KT > 1) issue_all(1, 1);
+  bool waited = false;
+  if constexpr (NST == 3) {
+    if (KT > 2) {
+      issue_all(2, 2);
+      wait_vm_lgkm0<2 * LPW>();
+      waited = true;
+    }
+  }
+  if (!waited) {
+    if (KT > 1) wait_vm_lgkm0<LPW>(); else wait_vm_lgkm0<0>();
+  }
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
-  if (KT > 1) {
-#pragma unroll
-    for (int j = 0; j < LPW; ++j) issue_one(1, j, FBK * 2);
-  }
   read_frags(0, 0, a0, b0);
-  // One k-step.  DMA: prefetch tile kt+2 into the stage being vacated.  NEXT: a tile kt+1 exists.
-  auto k_step = [&](int kt, auto dma_c, auto next_c) {
-    constexpr bool DMA = decltype(dma_c)::value, NEXT = decltype(next_c)::value;
-    const int cur = kt & 1;
+  // One k-step on stage `cur`.  DMA: issue tile kt+NST into the stage being vacated.
+  // YOUNGER: a batch younger than tile kt+1 is in flight at the barrier (it may stay in flight).
+  // NEXT: tile kt+1 exists.
+  auto k_step = [&](int kt, int cur, auto dma_c, auto younger_c, auto next_c) {
+    constexpr bool DMA = decltype(dma_c)::value, YOUNGER = decltype(younger_c)::value,
+                   NEXT = decltype(next_c)::value;
+    const int nxt = (cur + 1 == NST) ? 0 : cur + 1;
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): a0/b0 have arrived
     read_frags(cur, 1, a1, b1);
@@ -167,16 +194,16 @@ __device__ __forceinline__ void gemm_mainloop(__amdgpu_buffer_rsrc_t rA, __amdgp
     mma(a0, b0);
     __builtin_amdgcn_sched_barrier(0);
     // every read of stage cur is issued: wait for them and for this wave's share of tile kt+1
-    __builtin_amdgcn_s_waitcnt(0x0070);
+    if constexpr (YOUNGER) wait_vm_lgkm0<LPW>(); else wait_vm_lgkm0<0>();
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    if constexpr (NEXT) read_frags(cur ^ 1, 0, a0, b0);
+    if constexpr (NEXT) read_frags(nxt, 0, a0, b0);
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (DMA) {
-      const int kbytes = (kt + 2) * FBK * 2;
+      const int kbytes = (kt + NST) * FBK * 2;
 #pragma unroll
       for (int t = 0; t < MI * NI; ++t) {
-        acc[t / NI][t % NI] = mfma_32x32x16(a1[t / NI], b1[t % NI], acc[t / NI][t % NI]);
+        acc[t / NI][t % NI] = mfma_32x32x16(b1[t % NI], a1[t / NI], acc[t / NI][t % NI]);
         if (t < LPW) issue_one(cur, t, kbytes);
       }
 #pragma unroll
@@ -192,13 +219,29 @@ __device__ __forceinline__ void gemm_mainloop(__amdgpu_buffer_rsrc_t rA, __amdgp
   };
   using T_ = std::integral_constant<bool, true>;
   using F_ = std::integral_constant<bool, false>;
-  int kt = 0;
-  for (; kt + 2 < KT; ++kt) k_step(kt, T_{}, T_{});
-  if (kt + 1 < KT) {
-    k_step(kt, F_{}, T_{});
+  int kt = 0, cur = 0;
+  auto advance = [&]() {
     ++kt;
+    cur = (cur + 1 == NST) ? 0 : cur + 1;
+  };
+  if constexpr (NST == 2) {
+    for (; kt + 2 < KT; advance()) k_step(kt, cur, T_{}, F_{}, T_{});
+    if (kt + 1 < KT) {
+      k_step(kt, cur, F_{}, F_{}, T_{});
+      advance();
+    }
+  } else {
+    for (; kt + 3 < KT; advance()) k_step(kt, cur, T_{}, T_{}, T_{});
+    if (kt + 2 < KT) {
+      k_step(kt, cur, F_{}, T_{}, T_{});
+      advance();
+    }
+    if (kt + 1 < KT) {
+      k_step(kt, cur, F_{}, F_{}, T_{});
+      advance();
+    }
   }
-  k_step(kt, F_{}, F_{});
+  k_step(kt, cur, F_{}, F_{}, F_{});
 }
 
 template <int MI>
@@ -251,20 +294,33 @@ __device__ __forceinline__ void gemm1_tile(const bf16_t* __restrict__ xp, const 
                  voff + MI);
   f32x16 acc[MI][2];
   zero_acc<MI>(acc);
-  gemm_mainloop<MI>(rA, rB, voff, H, smem, wv, lane, acc);
+  gemm_mainloop<MI, (MI == 4 ? 2 : 3)>(rA, rB, voff, H, smem, wv, lane, acc);
 
-  const int col = n0 + 32 * wn + mfma32_col(lane);
+  // The weight fragment is the MFMA's row operand, so accumulator registers 4q..4q+3 of a lane
+  // are four consecutive output columns of one output row: one 8-byte store each.
+  const int row_in = 32 * MI * wm + (lane & 31);
 #pragma unroll
-  for (int mi = 0; mi < MI; ++mi)
+  for (int mi = 0; mi < MI; ++mi) {
+    const int row = row_in + 32 * mi;
+    if (row < rows) {
+      bf16_t* dst = hbuf + static_cast<size_t>(row0 + row) * F + n0 + 32 * wn + 4 * (lane >> 5);
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      int row = 32 * MI * wm + 32 * mi + mfma32_row(r, lane);
-      if (row < rows && col < F) {
-        float g = acc[mi][0][r], u = acc[mi][1][r];
-        float hval = g / (1.f + __expf(-g)) * u;
-        hbuf[static_cast<size_t>(row0 + row) * F + col] = f32_to_bf16(hval);
+      for (int q = 0; q < 4; ++q) {
+        if (n0 + 32 * wn + 8 * q < F) {  // F % 8 == 0: an 8-column group is in or out as a whole
+          float hv[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            float g = acc[mi][0][4 * q + e], u = acc[mi][1][4 * q + e];
+            hv[e] = g / (1.f + __expf(-g)) * u;
+          }
+          uint2 pk;
+          pk.x = pack_bf16x2(hv[0], hv[1]);
+          pk.y = pack_bf16x2(hv[2], hv[3]);
+          *reinterpret_cast<uint2*>(dst + 8 * q) = pk;
+        }
       }
     }
+  }
 }
 
 // grid.x = ceil(F/128) column blocks (128 gate + 128 up weight rows each), grid.y = tile capacity.
@@ -283,8 +339,10 @@ __global__ __launch_bounds__(512, 2) void ffn_gemm1_kernel(const bf16_t* __restr
   const bf16_t* w13 = static_cast<const bf16_t*>(w13_ptrs[slot]);
   if (height > 128)
     gemm1_tile<4>(xp, w13, row0, row_end, n0, H, F, hbuf, smem);
-  else
+  else if (height > 64)
     gemm1_tile<2>(xp, w13, row0, row_end, n0, H, F, hbuf, smem);
+  else
+    gemm1_tile<1>(xp, w13, row0, row_end, n0, H, F, hbuf, smem);
 #endif
 }
 
@@ -304,19 +362,29 @@ __device__ __forceinline__ void gemm2_tile(const bf16_t* __restrict__ hbuf, cons
   dma_offsets<4>(wv, lane, F * 2, [&](int j) { return min(n0 + j, H - 1); }, voff + MI);
   f32x16 acc[MI][2];
   zero_acc<MI>(acc);
-  gemm_mainloop<MI>(rA, rB, voff, F, smem, wv, lane, acc);
+  gemm_mainloop<MI, (MI == 4 ? 2 : 3)>(rA, rB, voff, F, smem, wv, lane, acc);
 
+  const int row_in = 32 * MI * wm + (lane & 31);
 #pragma unroll
-  for (int mi = 0; mi < MI; ++mi)
+  for (int mi = 0; mi < MI; ++mi) {
+    const int row = row_in + 32 * mi;
+    if (row < rows) {
 #pragma unroll
-    for (int ni = 0; ni < 2; ++ni) {
-      int col = n0 + 64 * wn + 32 * ni + mfma32_col(lane);
+      for (int ni = 0; ni < 2; ++ni) {
+        const int cbase = n0 + 64 * wn + 32 * ni;
+        bf16_t* dst = y + static_cast<size_t>(row0 + row) * H + cbase + 4 * (lane >> 5);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        int row = 32 * MI * wm + 32 * mi + mfma32_row(r, lane);
-        if (row < rows && col < H) y[static_cast<size_t>(row0 + row) * H + col] = f32_to_bf16(acc[mi][ni][r]);
+        for (int q = 0; q < 4; ++q) {
+          if (cbase + 8 * q < H) {
+            uint2 pk;
+            pk.x = pack_bf16x2(acc[mi][ni][4 * q], acc[mi][ni][4 * q + 1]);
+            pk.y = pack_bf16x2(acc[mi][ni][4 * q + 2], acc[mi][ni][4 * q + 3]);
+            *reinterpret_cast<uint2*>(dst + 8 * q) = pk;
+          }
+        }
       }
     }
+  }
 }
 
 // grid.x = ceil(H/256) column blocks, grid.y = tile capacity.
@@ -335,8 +403,10 @@ __global__ __launch_bounds__(512, 2) void ffn_gemm2_kernel(const bf16_t* __restr
   const bf16_t* w2 = static_cast<const bf16_t*>(w2_ptrs[slot]);
   if (height > 128)
     gemm2_tile<4>(hbuf, w2, row0, row_end, n0, H, F, y, smem);
-  else
+  else if (height > 64)
     gemm2_tile<2>(hbuf, w2, row0, row_end, n0, H, F, y, smem);
+  else
+    gemm2_tile<1>(hbuf, w2, row0, row_end, n0, H, F, y, smem);
 #endif
 }
 

@@ -21,8 +21,8 @@
 namespace probe {
 
 constexpr int kPermWaves = 4;                 // waves per workgroup in steps 1 and 3
-constexpr int kSegPairs = 1024;               // pairs per wave segment
-constexpr int kSegIters = kSegPairs / kWave;  // 16 wave-wide iterations per segment
+constexpr int kSegPairs = 256;                // pairs per wave segment
+constexpr int kSegIters = kSegPairs / kWave;  // 4 wave-wide iterations per segment
 
 __device__ __forceinline__ uint64_t lanemask_lt() {
   int l = lane_id();
@@ -62,72 +62,109 @@ __global__ __launch_bounds__(kPermWaves* kWave) void permute_hist_kernel(
     for (int e = lane; e < E; e += kWave) seg_hist[static_cast<long>(seg) * E + e] = cnt_w[e];
 }
 
-// Step 2.  One workgroup of 256 threads; thread e owns expert e.
-__global__ __launch_bounds__(256) void permute_scan_kernel(
+// Step 2.  One workgroup of 1024 threads: expert e = tid % 256 is scanned by four threads, each
+// over a quarter of the segments (sum pass, then a pass that writes the exclusive bases).
+__global__ __launch_bounds__(1024) void permute_scan_kernel(
     int32_t* __restrict__ seg_hist /* in: counts, out: exclusive bases */, int U, int E,
     const int32_t* __restrict__ rep_off, const int32_t* __restrict__ rep_slot,
     const int32_t* __restrict__ rep_weight, int S, int32_t* __restrict__ slot_counts,
     int32_t* __restrict__ slot_offsets, int32_t* __restrict__ n_local) {
   __shared__ int32_t sc[PROBE_MAX_SLOTS];
+  __shared__ int32_t part_tot[4][PROBE_MAX_EXPERTS];
   __shared__ int32_t wave_tot[4];
-  int tid = threadIdx.x;
-  for (int s = tid; s < S; s += 256) sc[s] = 0;
+  const int tid = threadIdx.x;
+  const int e = tid & 255, part = tid >> 8;
+  const int chunk = (U + 3) / 4;
+  const int u0 = min(part * chunk, U), u1 = min(u0 + chunk, U);
+  for (int s = tid; s < S; s += 1024) sc[s] = 0;
+  int tot = 0;
+  if (e < E) {
+    int u = u0;
+    for (; u + 16 <= u1; u += 16) {  // sixteen independent loads in flight
+      int c[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) c[i] = seg_hist[static_cast<long>(u + i) * E + e];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) tot += c[i];
+    }
+    for (; u < u1; ++u) tot += seg_hist[static_cast<long>(u) * E + e];
+  }
+  part_tot[part][e] = tot;
   __syncthreads();
-  if (tid < E) {
+  if (e < E) {
     int run = 0;
-    for (int u = 0; u < U; ++u) {
-      long i = static_cast<long>(u) * E + tid;
+    for (int q = 0; q < part; ++q) run += part_tot[q][e];
+    int u = u0;
+    for (; u + 16 <= u1; u += 16) {
+      int c[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) c[i] = seg_hist[static_cast<long>(u + i) * E + e];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        seg_hist[static_cast<long>(u + i) * E + e] = run;
+        run += c[i];
+      }
+    }
+    for (; u < u1; ++u) {
+      long i = static_cast<long>(u) * E + e;
       int c = seg_hist[i];
       seg_hist[i] = run;
       run += c;
     }
+  }
+  if (part == 0 && e < E) {
+    const int n_e = part_tot[0][e] + part_tot[1][e] + part_tot[2][e] + part_tot[3][e];
     // rows each replica of this expert receives: floor(n/P) w_i + clamp(n mod P - c_{i-1}, 0, w_i)
-    int lo = rep_off[tid], hi = rep_off[tid + 1];
+    int lo = rep_off[e], hi = rep_off[e + 1];
     int P = 0;
     for (int i = lo; i < hi; ++i) P += rep_weight[i];
     if (P > 0) {
-      int full = run / P, rem = run - full * P, cum = 0;
+      int full = n_e / P, rem = n_e - full * P, cum = 0;
       for (int i = lo; i < hi; ++i) {
         int wgt = rep_weight[i];
-        int part = min(max(rem - cum, 0), wgt);
+        int part_rows = min(max(rem - cum, 0), wgt);
         int slot = rep_slot[i];
-        if (slot >= 0 && slot < S) sc[slot] = full * wgt + part;
+        if (slot >= 0 && slot < S) sc[slot] = full * wgt + part_rows;
         cum += wgt;
       }
     }
   }
   __syncthreads();
-  // exclusive prefix sum over S <= 1024 slots: 4 consecutive slots per thread
-  int v[4], local = 0;
+  // exclusive prefix sum over S <= 1024 slots: 4 consecutive slots per thread, first 256 threads
+  int v[4] = {0, 0, 0, 0}, local = 0, incl = 0;
+  if (tid < 256) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    int s = tid * 4 + i;
-    v[i] = s < S ? sc[s] : 0;
-    local += v[i];
-  }
-  int incl = local;
-#pragma unroll
-  for (int d = 1; d < kWave; d <<= 1) {
-    int o = __shfl_up(incl, d, kWave);
-    if (lane_id() >= d) incl += o;
-  }
-  if (lane_id() == kWave - 1) wave_tot[tid / kWave] = incl;
-  __syncthreads();
-  int wave_base = 0;
-  for (int i = 0; i < tid / kWave; ++i) wave_base += wave_tot[i];
-  int excl = wave_base + incl - local;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    int s = tid * 4 + i;
-    if (s < S) {
-      slot_counts[s] = v[i];
-      slot_offsets[s] = excl;
+    for (int i = 0; i < 4; ++i) {
+      int s = tid * 4 + i;
+      v[i] = s < S ? sc[s] : 0;
+      local += v[i];
     }
-    excl += v[i];
+    incl = local;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+      int o = __shfl_up(incl, d, kWave);
+      if (lane_id() >= d) incl += o;
+    }
+    if (lane_id() == kWave - 1) wave_tot[tid / kWave] = incl;
   }
-  if (tid == 255) {
-    slot_offsets[S] = excl;
-    n_local[0] = excl;
+  __syncthreads();
+  if (tid < 256) {
+    int wave_base = 0;
+    for (int i = 0; i < tid / kWave; ++i) wave_base += wave_tot[i];
+    int excl = wave_base + incl - local;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int s = tid * 4 + i;
+      if (s < S) {
+        slot_counts[s] = v[i];
+        slot_offsets[s] = excl;
+      }
+      excl += v[i];
+    }
+    if (tid == 255) {
+      slot_offsets[S] = excl;
+      n_local[0] = excl;
+    }
   }
 }
 
@@ -138,13 +175,25 @@ __global__ __launch_bounds__(kPermWaves* kWave) void permute_index_kernel(
     const int32_t* __restrict__ rep_weight, const int32_t* __restrict__ slot_offsets, int S,
     int32_t* __restrict__ pair_row, int32_t* __restrict__ row_pair) {
   __shared__ int32_t cnt_mem[kPermWaves][PROBE_MAX_EXPERTS];
+  __shared__ int32_t e_lo[PROBE_MAX_EXPERTS], e_hi[PROBE_MAX_EXPERTS], e_P[PROBE_MAX_EXPERTS];
+  __shared__ int32_t s_off[PROBE_MAX_SLOTS + 1];
   int w = threadIdx.x / kWave, lane = lane_id();
   volatile int32_t* cnt_w = cnt_mem[w];  // volatile: keep every lane's read before the leader's update
   int seg = blockIdx.x * kPermWaves + w;
   long base = static_cast<long>(seg) * kSegPairs;
+  // the plan, once per workgroup: replica range and total weight of every expert, slot offsets
+  for (int e = threadIdx.x; e < E; e += kPermWaves * kWave) {
+    int lo = rep_off[e], hi = rep_off[e + 1], P = 0;
+    for (int i = lo; i < hi; ++i) P += rep_weight[i];
+    e_lo[e] = lo;
+    e_hi[e] = hi;
+    e_P[e] = P;
+  }
+  for (int i = threadIdx.x; i <= S; i += kPermWaves * kWave) s_off[i] = slot_offsets[i];
   if (base < N)
     for (int e = lane; e < E; e += kWave) cnt_w[e] = seg_base[static_cast<long>(seg) * E + e];
-  int n_loc = slot_offsets[S];
+  __syncthreads();
+  int n_loc = s_off[S];
   for (int it = 0; it < kSegIters; ++it) {
     long p = base + it * kWave + lane;
     int e = p < N ? topk_idx[p] : -1;
@@ -157,9 +206,7 @@ __global__ __launch_bounds__(kPermWaves* kWave) void permute_index_kernel(
     if (valid) {
       int before = __popcll(m & lanemask_lt());
       int j = cnt_w[e] + before;                       // arrival rank of this pair for expert e
-      int lo = rep_off[e], hi = rep_off[e + 1];
-      int P = 0;
-      for (int i = lo; i < hi; ++i) P += rep_weight[i];
+      int lo = e_lo[e], hi = e_hi[e], P = e_P[e];
       int row = -1;
       if (P > 0) {
         int full = j / P, u = j - full * P, cum = 0;
@@ -167,7 +214,7 @@ __global__ __launch_bounds__(kPermWaves* kWave) void permute_index_kernel(
           int wgt = rep_weight[i];
           if (u < cum + wgt) {
             int slot = rep_slot[i];
-            if (slot >= 0 && slot < S) row = slot_offsets[slot] + full * wgt + (u - cum);
+            if (slot >= 0 && slot < S) row = s_off[slot] + full * wgt + (u - cum);
             if (row >= N) row = -1;  // only an inconsistent plan (two replicas in one slot) gets here
             break;
           }
@@ -253,7 +300,7 @@ extern "C" int probe_permute(const int32_t* topk_idx, const probe_plan* plan, co
   if (U > 0)
     hipLaunchKernelGGL(permute_hist_kernel, dim3(seg_blocks), dim3(kPermWaves * kWave), 0, st, topk_idx, N,
                        E, seg);
-  hipLaunchKernelGGL(permute_scan_kernel, dim3(1), dim3(256), 0, st, seg, U, E, plan->rep_off,
+  hipLaunchKernelGGL(permute_scan_kernel, dim3(1), dim3(1024), 0, st, seg, U, E, plan->rep_off,
                      plan->rep_slot, plan->rep_weight, S, slot_counts, slot_offsets, n_local);
   if (U > 0) {
     hipLaunchKernelGGL(permute_index_kernel, dim3(seg_blocks), dim3(kPermWaves * kWave), 0, st, topk_idx,

@@ -11,8 +11,8 @@
 //   2. gemm     split-K tiled GEMM (128 tokens x 128 experts x 64 k per step, 4 waves of
 //               64x64, LDS-staged with register prefetch), three MFMAs per operand pair
 //               (one per plane) into one accumulator               -> partial[KS][T][E] fp32
-//   3. softmax  one wave per token: sum the KS partials in fixed order, add the bias, softmax
-//               over E, k rounds of wave arg-max (ties to the lower index), weights, counts
+//   3. softmax  sixteen lanes per token: sum the KS partials in fixed order, add the bias,
+//               softmax over E, k rounds of row arg-max (ties to the lower index), weights, counts
 #include <limits.h>
 
 #include "common.hpp"
@@ -134,98 +134,177 @@ __global__ __launch_bounds__(256, 2) void gate_gemm_kernel(const bf16_t* __restr
 }
 
 // ---- 3. softmax + top-k ---------------------------------------------------------------
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+// Sixteen lanes (one DPP row) own one token, a wave owns four.  Lane `sub` of a row holds the
+// experts 64*i + 4*sub + j (i < NV, j < 4), i.e. 16-byte pieces of the logit row, so partial
+// sums are read with float4 loads and every reduction stays inside a row: four rotate-and-
+// combine DPP steps give all 16 lanes the same result bit for bit.
+template <int N>
+__device__ __forceinline__ float dpp_ror(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x120 | N, 0xf, 0xf, false));
+}
+template <int N>
+__device__ __forceinline__ int dpp_ror(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, 0x120 | N, 0xf, 0xf, false);
+}
+__device__ __forceinline__ float row_max(float v) {
+  v = fmaxf(v, dpp_ror<8>(v));
+  v = fmaxf(v, dpp_ror<4>(v));
+  v = fmaxf(v, dpp_ror<2>(v));
+  v = fmaxf(v, dpp_ror<1>(v));
   return v;
 }
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+__device__ __forceinline__ float row_sum(float v) {
+  v += dpp_ror<8>(v);
+  v += dpp_ror<4>(v);
+  v += dpp_ror<2>(v);
+  v += dpp_ror<1>(v);
   return v;
+}
+// arg-max of (value, expert): larger value wins, equal values go to the lower expert id
+template <int N>
+__device__ __forceinline__ void argmax_step(float& v, int& e) {
+  float ov = dpp_ror<N>(v);
+  int oe = dpp_ror<N>(e);
+  bool take = (oe != INT_MAX) && (e == INT_MAX || ov > v || (ov == v && oe < e));
+  v = take ? ov : v;
+  e = take ? oe : e;
 }
 
-// VPT = experts per lane (lane owns experts lane, lane+64, ...), E <= 64*VPT.
-template <int VPT>
+template <int NV>
 __global__ __launch_bounds__(256) void gate_softmax_topk_kernel(
     const float* __restrict__ partial, int KS, const float* __restrict__ bias, int G, int tpg, int T,
     int E, int k, int renorm, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
     float* __restrict__ probs, int32_t* __restrict__ counts) {
   __shared__ int32_t hist[PROBE_MAX_EXPERTS];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int sub = lane & 15, grp = lane >> 4;
   hist[tid] = 0;
   __syncthreads();
   const float ninf = -__builtin_inff();
-  for (int t = blockIdx.x * 4 + wv; t < T; t += gridDim.x * 4) {
+  const bool vec = (E & 3) == 0;
+  const int tokens_per_pass = gridDim.x * 16;
+  for (int t = (blockIdx.x * 4 + wv) * 4 + grp; t < T + 3; t += tokens_per_pass) {
+    // the four rows of a wave run in lock step; rows past T compute on a clamped token and skip stores
+    const bool live = t < T;
+    const int tt = live ? t : T - 1;
     int g = 0;
-    if (bias) g = min(t / tpg, G - 1);
-    float l[VPT], p[VPT];
-    float mx = ninf;
+    if (bias) g = min(tt / tpg, G - 1);
+    float l[NV * 4], p[NV * 4];
+    if (vec) {
+      // all loads of a round of four split-K slices are issued before any is consumed
+      float4 accv[NV];
 #pragma unroll
-    for (int i = 0; i < VPT; ++i) {
-      int e = lane + 64 * i;
-      l[i] = ninf;
-      if (e < E) {
-        float s = 0.f;
-        for (int q = 0; q < KS; ++q) s += partial[(static_cast<long>(q) * T + t) * E + e];
-        if (bias) s += bias[static_cast<long>(g) * E + e];
-        l[i] = s;
+      for (int i = 0; i < NV; ++i) accv[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+      for (int q0 = 0; q0 < KS; q0 += 4) {
+        float4 tmp[4][NV];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int q = min(q0 + u, KS - 1);
+#pragma unroll
+          for (int i = 0; i < NV; ++i) {
+            const int e0 = min(64 * i + 4 * sub, E - 4);
+            tmp[u][i] = *reinterpret_cast<const float4*>(partial + (static_cast<long>(q) * T + tt) * E + e0);
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          if (q0 + u < KS) {
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+              accv[i].x += tmp[u][i].x; accv[i].y += tmp[u][i].y;
+              accv[i].z += tmp[u][i].z; accv[i].w += tmp[u][i].w;
+            }
+          }
       }
-      mx = fmaxf(mx, l[i]);
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        const int e0 = 64 * i + 4 * sub;
+        float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (bias && e0 < E) bv = *reinterpret_cast<const float4*>(bias + static_cast<long>(g) * E + e0);
+        l[4 * i] = (e0 < E) ? accv[i].x + bv.x : ninf;
+        l[4 * i + 1] = (e0 < E) ? accv[i].y + bv.y : ninf;
+        l[4 * i + 2] = (e0 < E) ? accv[i].z + bv.z : ninf;
+        l[4 * i + 3] = (e0 < E) ? accv[i].w + bv.w : ninf;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < NV; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int e = 64 * i + 4 * sub + j;
+          float sacc = 0.f;
+          if (e < E) {
+            for (int q = 0; q < KS; ++q) sacc += partial[(static_cast<long>(q) * T + tt) * E + e];
+            if (bias) sacc += bias[static_cast<long>(g) * E + e];
+          }
+          l[4 * i + j] = (e < E) ? sacc : ninf;
+        }
     }
-    mx = wave_max(mx);
+    float mx = l[0];
+#pragma unroll
+    for (int i = 1; i < NV * 4; ++i) mx = fmaxf(mx, l[i]);
+    mx = row_max(mx);
     float sum = 0.f;
 #pragma unroll
-    for (int i = 0; i < VPT; ++i) {
-      p[i] = (lane + 64 * i < E) ? expf(l[i] - mx) : 0.f;
+    for (int i = 0; i < NV * 4; ++i) {
+      p[i] = (l[i] == ninf) ? 0.f : expf(l[i] - mx);
       sum += p[i];
     }
-    sum = wave_sum(sum);
+    sum = row_sum(sum);
     const float inv = 1.f / sum;
 #pragma unroll
-    for (int i = 0; i < VPT; ++i) {
-      p[i] *= inv;
-      if (probs && lane + 64 * i < E) probs[static_cast<long>(t) * E + lane + 64 * i] = p[i];
+    for (int i = 0; i < NV * 4; ++i) p[i] *= inv;
+    if (probs && live) {
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        const int e0 = 64 * i + 4 * sub;
+        if (vec) {
+          if (e0 < E)
+            *reinterpret_cast<float4*>(probs + static_cast<long>(t) * E + e0) =
+                make_float4(p[4 * i], p[4 * i + 1], p[4 * i + 2], p[4 * i + 3]);
+        } else {
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            if (e0 + j < E) probs[static_cast<long>(t) * E + e0 + j] = p[4 * i + j];
+        }
+      }
     }
     unsigned taken = 0;
     int isel = 0;
     float wsel = 0.f, wtot = 0.f;
     for (int s = 0; s < k; ++s) {
-      float bv = ninf;
+      float bv = ninf, bp = 0.f;
       int be = INT_MAX;
 #pragma unroll
-      for (int i = 0; i < VPT; ++i) {
-        int e = lane + 64 * i;
-        if (e < E && !((taken >> i) & 1u) && (be == INT_MAX || l[i] > bv)) {
-          bv = l[i];
-          be = e;
-        }
+      for (int i = 0; i < NV * 4; ++i) {
+        const int e = 64 * (i >> 2) + 4 * sub + (i & 3);
+        const bool ok = e < E && !((taken >> i) & 1u) && (be == INT_MAX || l[i] > bv);
+        bv = ok ? l[i] : bv;
+        bp = ok ? p[i] : bp;
+        be = ok ? e : be;
       }
-#pragma unroll
-      for (int o = 32; o > 0; o >>= 1) {
-        float ov = __shfl_xor(bv, o, kWave);
-        int oe = __shfl_xor(be, o, kWave);
-        if (oe != INT_MAX && (be == INT_MAX || ov > bv || (ov == bv && oe < be))) {
-          bv = ov;
-          be = oe;
-        }
+      const int mine = be;  // this lane's candidate
+      argmax_step<8>(bv, be);
+      argmax_step<4>(bv, be);
+      argmax_step<2>(bv, be);
+      argmax_step<1>(bv, be);
+      // the winner's probability: only its owner contributes, the row sum broadcasts it
+      const bool owner = (mine == be);
+      const float pw = row_sum(owner ? bp : 0.f);
+      if (owner) {
+        const int i = ((be >> 6) << 2) | (be & 3);
+        taken |= 1u << i;
       }
-      float pv = 0.f;
-#pragma unroll
-      for (int i = 0; i < VPT; ++i)
-        if (i == (be >> 6)) pv = p[i];
-      float pw = __shfl(pv, be & 63, kWave);
-      if (lane == (be & 63)) taken |= 1u << (be >> 6);
       wtot += pw;
-      if (lane == s) {
+      if (sub == s) {
         isel = be;
         wsel = pw;
       }
     }
     if (renorm) wsel /= wtot;
-    if (lane < k) {
-      topk_idx[static_cast<long>(t) * k + lane] = isel;
-      topk_w[static_cast<long>(t) * k + lane] = wsel;
+    if (live && sub < k) {
+      topk_idx[static_cast<long>(t) * k + sub] = isel;
+      topk_w[static_cast<long>(t) * k + sub] = wsel;
       if (counts) atomicAdd(&hist[isel], 1);
     }
   }
@@ -285,8 +364,8 @@ static int route_impl(const char* name, const void* x_bf16, const float* w_gate,
   if (T > 0) {
     hipLaunchKernelGGL(gate_gemm_kernel, dim3(sh.mt, sh.nt, sh.ks), dim3(256), 0, st,
                        static_cast<const bf16_t*>(x_bf16), planes, T, H, E, sh.k_chunk, partial);
-    int grid = (T + 3) / 4;
-    if (grid > 2048) grid = 2048;
+    int grid = (T + 15) / 16;
+    if (grid > 4096) grid = 4096;
     int G = bias ? bias_groups : 1, tpg = bias ? tokens_per_group : 1;
 #define PROBE_TOPK_LAUNCH(V)                                                                           \
   hipLaunchKernelGGL(gate_softmax_topk_kernel<V>, dim3(grid), dim3(256), 0, st, partial, sh.ks, bias, \

@@ -1,0 +1,106 @@
+"""Host-side checks of the C-ABI boundary that need no GPU: the library loads, exports every
+symbol the header declares, sizes its workspaces, and rejects bad arguments before launching
+anything.  No compute call is made here."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "probe.h")
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2602_00509_amd import probe, build
+    if not os.path.exists(probe.LIB_PATH):
+        build.build()
+    return probe.lib()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(probe_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(L):
+    names = declared_functions()
+    for must in ("probe_route_topk", "probe_predict_topk", "probe_permute", "probe_grouped_ffn",
+                 "probe_combine", "probe_last_error_string", "probe_version"):
+        assert must in names
+    for n in names:
+        assert hasattr(L, n), "libprobe.so does not export %s" % n
+    assert L.probe_version().decode()
+
+
+def test_workspace_sizes(L):
+    from paper_2602_00509_amd import probe
+    # route: three bf16 planes of the gate plus split-K partial logits
+    assert probe.route_topk_workspace_bytes(8192, 7168, 256, 8) >= 3 * 256 * 7168 * 2 + 8192 * 256 * 4
+    assert probe.route_topk_workspace_bytes(0, 64, 8, 2) > 0
+    assert probe.permute_workspace_bytes(8192, 256, 8, 36) >= 256 * 4
+    # ffn: the intermediate activation h [max_rows, F] in bf16
+    assert probe.grouped_ffn_workspace_bytes(36, 7168, 2048, 65536) >= 65536 * 2048 * 2
+
+
+def test_bad_arguments_are_rejected_without_a_launch(L):
+    from paper_2602_00509_amd.probe import _Plan
+    err = lambda: L.probe_last_error_string().decode()
+    fake = C.c_void_p(0x1000)          # aligned, never dereferenced: validation fails first
+    odd = C.c_void_p(0x1008)
+    big = C.c_size_t(1 << 40)
+    # combine
+    assert L.probe_combine(None, None, None, 4, 64, 2, None, None) == -1 and "null" in err()
+    assert L.probe_combine(fake, fake, fake, 4, 60, 2, fake, None) == -2
+    assert L.probe_combine(fake, fake, fake, 4, 64, 9, fake, None) == -2
+    assert L.probe_combine(odd, fake, fake, 4, 64, 2, fake, None) == -3
+    assert L.probe_combine(fake, fake, fake, -1, 64, 2, fake, None) == -1
+    assert L.probe_combine(None, None, None, 0, 64, 2, None, None) == 0          # empty batch is legal
+    # route / predict
+    for fn in (L.probe_route_topk, L.probe_predict_topk):
+        assert fn(fake, fake, None, 1, 1, 16, 64, 8, 9, 1, fake, fake, None, None, fake, big, None) == -1   # k > E
+        assert fn(fake, fake, None, 1, 1, 16, 64, 300, 2, 1, fake, fake, None, None, fake, big, None) == -2  # E > 256
+        assert fn(fake, fake, None, 1, 1, 16, 60, 8, 2, 1, fake, fake, None, None, fake, big, None) == -2    # H % 8
+        assert fn(odd, fake, None, 1, 1, 16, 64, 8, 2, 1, fake, fake, None, None, fake, big, None) == -3
+        assert fn(fake, fake, None, 1, 1, 16, 64, 8, 2, 1, fake, fake, None, None, fake, C.c_size_t(16), None) == -4
+        assert fn(fake, fake, fake, 0, 1, 16, 64, 8, 2, 1, fake, fake, None, None, fake, big, None) == -1    # G < 1
+        assert "probe_" in err()
+    # permute
+    plan = _Plan(0x1000, 0x1000, 0x1000, 4)
+    args = lambda **kw: None
+    assert L.probe_permute(fake, None, fake, 16, 64, 8, 2, fake, fake, fake, fake, fake, fake, fake, big, None) == -1
+    assert L.probe_permute(fake, C.byref(plan), fake, 16, 60, 8, 2, fake, fake, fake, fake, fake, fake, fake, big, None) == -2
+    assert L.probe_permute(fake, C.byref(plan), fake, 16, 64, 8, 2, fake, fake, fake, fake, fake, fake, fake, C.c_size_t(0), None) == -4
+    bad = _Plan(0x1000, 0x1000, 0x1000, 2000)
+    assert L.probe_permute(fake, C.byref(bad), fake, 16, 64, 8, 2, fake, fake, fake, fake, fake, fake, fake, big, None) == -2
+    # grouped ffn
+    assert L.probe_grouped_ffn(fake, fake, fake, fake, 4, 100, 128, 64, fake, fake, big, None) == -2      # H % 64
+    assert L.probe_grouped_ffn(fake, fake, fake, fake, 4, 128, 96, 64, fake, fake, big, None) == -2       # F % 64
+    assert L.probe_grouped_ffn(fake, fake, fake, fake, 0, 128, 128, 64, fake, fake, big, None) == -1
+    assert L.probe_grouped_ffn(None, fake, fake, fake, 4, 128, 128, 64, fake, fake, big, None) == -1
+    assert L.probe_grouped_ffn(fake, fake, fake, fake, 4, 128, 128, 64, fake, fake, C.c_size_t(8), None) == -4
+    assert L.probe_grouped_ffn(fake, fake, fake, fake, 4, 128, 128, 0, fake, None, C.c_size_t(0), None) == 0  # no rows
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    from paper_2602_00509_amd import probe
+    monkeypatch.setattr(probe, "_lib", None)
+    monkeypatch.setattr(probe, "LIB_PATH", "/nonexistent/libprobe.so")
+    with pytest.raises(FileNotFoundError):
+        probe.lib()
+
+
+def test_product_path_does_not_touch_the_oracle():
+    """The binding, the kernels' build script and the workload generators never import oracle/."""
+    pkg = os.path.join(ROOT, "paper_2602_00509_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text and "probe_oracle" not in text, f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c")):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2602_00509_amd" not in text and "libprobe.so" not in text, f
