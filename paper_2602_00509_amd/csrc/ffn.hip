@@ -42,57 +42,79 @@ constexpr int kFfnLdsBytes = 3 * (128 + 256) * 128;  // 144 KB >= 2 * (256 + 256
 // ---- 0. schedule ----------------------------------------------------------------------
 // table[0] = number of tiles; tile i: table[1+3i] = slot, table[2+3i] = first row,
 // table[3+3i] = tile height (256, 128 or 64).  A slot of M rows gets floor(M/256) tall tiles
-// and, for the remainder r, one more tile of the smallest height that holds r.
-__device__ __forceinline__ int slot_tiles(int m) { return m / 256 + ((m % 256) ? 1 : 0); }
+// and, for the remainder r, one more tile of the smallest height that holds r.  Tiles are
+// listed tallest first (all 256-row tiles, then the 128s, then the 64s), so that the long
+// workgroups start early and the short ones fill the tail of the launch.
+__device__ __forceinline__ int tiles_of_class(int m, int cls) {
+  const int r = m & 255;
+  if (cls == 0) return (m >> 8) + (r > 128 ? 1 : 0);
+  if (cls == 1) return (r > 64 && r <= 128) ? 1 : 0;
+  return (r > 0 && r <= 64) ? 1 : 0;
+}
 
 __global__ __launch_bounds__(256) void ffn_schedule_kernel(const int32_t* __restrict__ slot_offsets,
                                                            int S, int max_tiles,
                                                            int32_t* __restrict__ table) {
-  __shared__ int32_t tile_start[PROBE_MAX_SLOTS + 1];
+  __shared__ int32_t start[3][PROBE_MAX_SLOTS + 1];  // exclusive prefix of tiles per class
   __shared__ int32_t wave_tot[4];
   const int tid = threadIdx.x, lane = tid & 63;
-  int v[4], local = 0;
+  int m[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     int s = tid * 4 + i;
-    int m = 0;
-    if (s < S) m = max(slot_offsets[s + 1] - slot_offsets[s], 0);
-    v[i] = slot_tiles(m);
-    local += v[i];
+    m[i] = (s < S) ? max(slot_offsets[s + 1] - slot_offsets[s], 0) : 0;
   }
-  int incl = local;
+  for (int cls = 0; cls < 3; ++cls) {
+    int v[4], local = 0;
 #pragma unroll
-  for (int d = 1; d < kWave; d <<= 1) {
-    int o = __shfl_up(incl, d, kWave);
-    if (lane >= d) incl += o;
-  }
-  if (lane == kWave - 1) wave_tot[tid >> 6] = incl;
-  __syncthreads();
-  int excl = incl - local;
-  for (int i = 0; i < (tid >> 6); ++i) excl += wave_tot[i];
+    for (int i = 0; i < 4; ++i) {
+      v[i] = tiles_of_class(m[i], cls);
+      local += v[i];
+    }
+    int incl = local;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    int s = tid * 4 + i;
-    if (s < S) tile_start[s] = excl;
-    excl += v[i];
+    for (int d = 1; d < kWave; d <<= 1) {
+      int o = __shfl_up(incl, d, kWave);
+      if (lane >= d) incl += o;
+    }
+    __syncthreads();  // wave_tot of the previous class has been consumed
+    if (lane == kWave - 1) wave_tot[tid >> 6] = incl;
+    __syncthreads();
+    int excl = incl - local;
+    for (int i = 0; i < (tid >> 6); ++i) excl += wave_tot[i];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int s = tid * 4 + i;
+      if (s < S) start[cls][s] = excl;
+      excl += v[i];
+    }
+    if (tid == 255) start[cls][S] = excl;  // the last thread's running sum is the class total
   }
-  if (tid == 255) tile_start[S] = excl;  // the last thread's running sum is the total
   __syncthreads();
-  int total = min(tile_start[S], max_tiles);
+  const int n0 = start[0][S], n1 = start[1][S], n2 = start[2][S];
+  const int total = min(n0 + n1 + n2, max_tiles);
   if (tid == 0) table[0] = total;
   for (int t = tid; t < total; t += 256) {
-    int lo = 0, hi = S;  // last slot with tile_start[slot] <= t
+    const int cls = t < n0 ? 0 : (t < n0 + n1 ? 1 : 2);
+    const int r = t - (cls == 0 ? 0 : (cls == 1 ? n0 : n0 + n1));
+    const int32_t* st = start[cls];
+    int lo = 0, hi = S;  // last slot with st[slot] <= r
     while (hi - lo > 1) {
       int mid = (lo + hi) >> 1;
-      if (tile_start[mid] <= t) lo = mid; else hi = mid;
+      if (st[mid] <= r) lo = mid; else hi = mid;
     }
-    int first = slot_offsets[lo], m = slot_offsets[lo + 1] - first;
-    int local_t = t - tile_start[lo];
-    int row0 = first + local_t * 256;
-    int left = m - local_t * 256;
+    const int first = slot_offsets[lo], rows = slot_offsets[lo + 1] - first;
+    int row0, height;
+    if (cls == 0) {
+      row0 = first + (r - st[lo]) * 256;
+      height = 256;
+    } else {
+      row0 = first + (rows & ~255);  // the remainder starts after the full tall tiles
+      height = cls == 1 ? 128 : 64;
+    }
     table[1 + 3 * t] = lo;
     table[2 + 3 * t] = row0;
-    table[3 + 3 * t] = left > 128 ? 256 : (left > 64 ? 128 : 64);
+    table[3 + 3 * t] = height;
   }
 }
 
