@@ -40,6 +40,9 @@ def main():
     ap.add_argument("--batches", type=int, default=0, help="distinct batches to rotate over (0 = config default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="after the timed steps, run a plain 1 GiB read + 1 GiB write elementwise kernel three "
+                         "times (reference for the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build is a one-GPU hot path (no collectives); run with --gpus 1")
@@ -195,6 +198,14 @@ def main():
                      "achieved": ffn_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": ffn_tflops / PEAK_BF16_TFLOPS, "traffic": None},
     }
+
+    if args.calibrate_copy:
+        src = torch.ones((1 << 28,), dtype=torch.float32, device=dev)      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, xs[0], wg, biases[0], tpg, plans[0], host_w, slot_experts[0],

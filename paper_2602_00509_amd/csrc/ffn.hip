@@ -293,6 +293,32 @@ __device__ __forceinline__ void dma_offsets(int wv, int lane, int row_bytes, Row
   }
 }
 
+// ---- workgroup -> (row tile, column block) -----------------------------------------------
+// Workgroups are dealt to the 8 XCDs round-robin by their linear id, and each XCD has its own
+// L2.  The launch is one-dimensional; workgroup L is the (L / 8)-th of XCD L % 8.  Work items
+// are numbered so that the 32 workgroups an XCD runs side by side form a compact 8 x 4 block
+// (8 consecutive row tiles x 4 consecutive column blocks): per k-step they pull 12 distinct
+// operand slices through that L2 instead of 18 for a 16 x 2 strip.
+constexpr int kXcds = 8, kBlkM = 8, kBlkN = 4, kBlk = kBlkM * kBlkN;
+
+__device__ __forceinline__ bool ffn_work_item(int n_tiles, int n_cols, int& tile, int& col) {
+  const int L = blockIdx.x;
+  const int xcd = L % kXcds, j = L / kXcds;
+  const int q = ((j / kBlk) * kXcds + xcd) * kBlk + (j % kBlk);  // item number: blocks of 32 per XCD
+  const int col_groups = (n_cols + kBlkN - 1) / kBlkN;
+  const int blk = q / kBlk, w = q % kBlk;
+  const int tg = blk / col_groups, cg = blk % col_groups;  // column groups vary fastest
+  tile = tg * kBlkM + w / kBlkN;
+  col = cg * kBlkN + w % kBlkN;
+  return tile < n_tiles && col < n_cols;
+}
+
+static int ffn_grid(int max_tiles, int n_cols) {
+  const int tile_groups = (max_tiles + kBlkM - 1) / kBlkM, col_groups = (n_cols + kBlkN - 1) / kBlkN;
+  const int blocks = tile_groups * col_groups;                       // blocks of 32 work items
+  return (blocks + kXcds - 1) / kXcds * kXcds * kBlk;                // whole rounds over the 8 XCDs
+}
+
 // ---- 1. gemm1 + SwiGLU ----------------------------------------------------------------
 template <int MI>
 __device__ __forceinline__ void gemm1_tile(const bf16_t* __restrict__ xp, const bf16_t* __restrict__ w13,
@@ -345,7 +371,8 @@ __device__ __forceinline__ void gemm1_tile(const bf16_t* __restrict__ xp, const 
   }
 }
 
-// grid.x = ceil(F/128) column blocks (128 gate + 128 up weight rows each), grid.y = tile capacity.
+// one-dimensional launch over (row tile, column block) work items; a column block is 128 gate +
+// 128 up weight rows
 __global__ __launch_bounds__(512, 2) void ffn_gemm1_kernel(const bf16_t* __restrict__ xp,
                                                            const int32_t* __restrict__ table,
                                                            const int32_t* __restrict__ slot_offsets,
@@ -353,11 +380,11 @@ __global__ __launch_bounds__(512, 2) void ffn_gemm1_kernel(const bf16_t* __restr
                                                            int H, int F, bf16_t* __restrict__ hbuf) {
 #if defined(__HIP_DEVICE_COMPILE__)
   extern __shared__ u32x4 smem[];
-  const int tile = blockIdx.y;
-  if (tile >= table[0]) return;
+  int tile, col;
+  if (!ffn_work_item(table[0], (F + 127) / 128, tile, col)) return;
   const int slot = table[1 + 3 * tile], row0 = table[2 + 3 * tile], height = table[3 + 3 * tile];
   const int row_end = slot_offsets[slot + 1];
-  const int n0 = blockIdx.x * 128;
+  const int n0 = col * 128;
   const bf16_t* w13 = static_cast<const bf16_t*>(w13_ptrs[slot]);
   if (height > 128)
     gemm1_tile<4>(xp, w13, row0, row_end, n0, H, F, hbuf, smem);
@@ -409,7 +436,7 @@ __device__ __forceinline__ void gemm2_tile(const bf16_t* __restrict__ hbuf, cons
   }
 }
 
-// grid.x = ceil(H/256) column blocks, grid.y = tile capacity.
+// one-dimensional launch over (row tile, column block of 256 output columns) work items
 __global__ __launch_bounds__(512, 2) void ffn_gemm2_kernel(const bf16_t* __restrict__ hbuf,
                                                            const int32_t* __restrict__ table,
                                                            const int32_t* __restrict__ slot_offsets,
@@ -417,11 +444,11 @@ __global__ __launch_bounds__(512, 2) void ffn_gemm2_kernel(const bf16_t* __restr
                                                            int H, int F, bf16_t* __restrict__ y) {
 #if defined(__HIP_DEVICE_COMPILE__)
   extern __shared__ u32x4 smem[];
-  const int tile = blockIdx.y;
-  if (tile >= table[0]) return;
+  int tile, col;
+  if (!ffn_work_item(table[0], (H + FBN - 1) / FBN, tile, col)) return;
   const int slot = table[1 + 3 * tile], row0 = table[2 + 3 * tile], height = table[3 + 3 * tile];
   const int row_end = slot_offsets[slot + 1];
-  const int n0 = blockIdx.x * FBN;
+  const int n0 = col * FBN;
   const bf16_t* w2 = static_cast<const bf16_t*>(w2_ptrs[slot]);
   if (height > 128)
     gemm2_tile<4>(hbuf, w2, row0, row_end, n0, H, F, y, smem);
@@ -493,17 +520,18 @@ extern "C" int probe_grouped_ffn(const void* xp_bf16, const int32_t* slot_offset
   PROBE_REQUIRE(workspace && aligned16(workspace) && workspace_bytes >= sh.h_bytes + sh.table_bytes,
                 PROBE_EWORKSPACE, "probe_grouped_ffn: workspace too small or misaligned (%zu < %zu)",
                 workspace_bytes, sh.h_bytes + sh.table_bytes);
-  PROBE_REQUIRE(sh.max_tiles <= 65535, PROBE_EUNSUPPORTED, "probe_grouped_ffn: max_rows too large (%d)",
-                max_rows);
+  PROBE_REQUIRE(static_cast<long>(sh.max_tiles + 8) * ((F + 127) / 128 + 4) < (1l << 30) &&
+                    static_cast<long>(sh.max_tiles + 8) * ((H + 255) / 256 + 4) < (1l << 30),
+                PROBE_EUNSUPPORTED, "probe_grouped_ffn: max_rows too large (%d)", max_rows);
   int rc = ffn_prepare();
   if (rc != PROBE_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   bf16_t* hbuf = static_cast<bf16_t*>(workspace);
   int32_t* table = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + sh.h_bytes);
   hipLaunchKernelGGL(ffn_schedule_kernel, dim3(1), dim3(256), 0, st, slot_offsets, S, sh.max_tiles, table);
-  hipLaunchKernelGGL(ffn_gemm1_kernel, dim3((F + 127) / 128, sh.max_tiles), dim3(512), kFfnLdsBytes, st,
+  hipLaunchKernelGGL(ffn_gemm1_kernel, dim3(ffn_grid(sh.max_tiles, (F + 127) / 128)), dim3(512), kFfnLdsBytes, st,
                      static_cast<const bf16_t*>(xp_bf16), table, slot_offsets, w13_ptrs, H, F, hbuf);
-  hipLaunchKernelGGL(ffn_gemm2_kernel, dim3((H + FBN - 1) / FBN, sh.max_tiles), dim3(512), kFfnLdsBytes, st,
+  hipLaunchKernelGGL(ffn_gemm2_kernel, dim3(ffn_grid(sh.max_tiles, (H + FBN - 1) / FBN)), dim3(512), kFfnLdsBytes, st,
                      hbuf, table, slot_offsets, w2_ptrs, H, F, static_cast<bf16_t*>(y_bf16));
   return check_launch("probe_grouped_ffn");
 }
