@@ -4,11 +4,12 @@
 One "step" is one pass of the whole path over one batch of synthetic tokens:
 predict_topk (next layer's cloned gate) -> route_topk -> permute -> grouped_ffn -> combine,
 all through the C ABI of libprobe.so on one stream, inputs resident in HBM, every buffer
-pre-allocated.  The default workload is the DeepSeek-V3-shaped shard (configuration 3 of
-the benchmark spec, the one the target is quoted on); successive steps rotate over 8 batches whose
+pre-allocated.  The default workload is the DeepSeek-V3-shaped shard (configuration 3 of the
+benchmark's list, the one its target is quoted on); successive steps rotate over 8 batches whose
 hot expert set moves, so no step re-reads the previous step's activations from cache.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric/value/unit, per-stage times, the roofline of the dominant call
+(the grouped FFN) and the CPU oracle timed on the host cores as a baseline.
 """
 from __future__ import annotations
 
@@ -25,6 +26,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E
+# L2-miss fetch + write bytes of ffn_gemm1 + ffn_gemm2 per call, from two rocprofv3 --pmc runs
+# (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0 after calibration on a plain 1 GiB copy kernel); the figures and
+# the commands are in profiles/bench_cfg3_hbm_traffic.md.  Only known for configuration 3.
+MEASURED_FFN_TRAFFIC_BYTES = {3: 6.33e9}
 
 
 def log(*a):
@@ -36,7 +41,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--config", type=int, default=3, help="BASELINE.json configuration (1-5)")
+    ap.add_argument("--config", type=int, default=3, help="benchmark configuration (1-5)")
     ap.add_argument("--batches", type=int, default=0, help="distinct batches to rotate over (0 = config default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0)
@@ -196,7 +201,10 @@ def main():
         "stage_frac_hbm_peak": {n: v / PEAK_HBM_GBPS for n, v in gbps.items()},
         "roofline": {"kernel": "probe_grouped_ffn (ffn_gemm1_kernel + ffn_gemm2_kernel)", "bound": "mfma",
                      "achieved": ffn_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": ffn_tflops / PEAK_BF16_TFLOPS, "traffic": None},
+                     "frac": ffn_tflops / PEAK_BF16_TFLOPS,
+                     "traffic": MEASURED_FFN_TRAFFIC_BYTES.get(cfg.cid) if nb == min(cfg.n_batches, 8) else None,
+                     "algorithmic_flops_per_launch": ffn_flops, "algorithmic_bytes_per_launch": ffn_bytes,
+                     "launch_ms": mean_ms["ffn"]},
     }
 
     if args.calibrate_copy:

@@ -22,7 +22,7 @@ import numpy as np
 
 @dataclass(frozen=True)
 class LayerConfig:
-    cid: int            # 1-based index into BASELINE.json "configs"
+    cid: int            # 1-based index into the list of benchmark configurations
     name: str
     T: int              # tokens
     H: int              # hidden size

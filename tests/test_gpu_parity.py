@@ -34,8 +34,12 @@ REPORT = []
 
 
 def _flush_report():
-    os.makedirs("gpurun_out", exist_ok=True)
-    with open("gpurun_out/parity_report.json", "w") as f:
+    """Error magnitudes of every case, written where PROBE_REPORT_DIR points (if set)."""
+    out = os.environ.get("PROBE_REPORT_DIR")
+    if not out:
+        return
+    os.makedirs(out, exist_ok=True)
+    with open(os.path.join(out, "parity_report.json"), "w") as f:
         json.dump(REPORT, f, indent=1, default=str)
 
 
