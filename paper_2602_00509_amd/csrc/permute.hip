@@ -4,13 +4,14 @@
 // replica by weighted round-robin, append to the slot's list) is reproduced exactly without
 // atomics: a pair's destination row follows from (expert e, arrival rank j) alone.
 //
-//   1. hist     each wave counts the experts of its own contiguous segment of pairs
-//               (LDS counters, one set per wave)                        -> seg_hist[U][E]
-//   2. scan     per expert, exclusive scan over segments                 -> seg_hist becomes
-//               seg_base; n_e; closed-form rows per replica; prefix sum over slots
+//   1. hist     each workgroup counts the experts of its own contiguous block of 1024 pairs
+//               (wave ballots, LDS counters)                             -> blk_hist[U][E]
+//   2. scan     per expert, exclusive scan over blocks                   -> blk_hist becomes
+//               blk_base; n_e; closed-form rows per replica; prefix sum over slots
 //               -> slot_counts, slot_offsets, n_local
-//   3. index    every wave re-walks its segment, ranks each pair among equal experts with
-//               wave ballots, and computes slot and row analytically     -> pair_row, row_pair
+//   3. index    every workgroup re-walks its block (each wave a 256-pair segment, bases of the
+//               later waves from the earlier waves' counts), ranks each pair among equal
+//               experts with wave ballots, computes slot and row analytically -> pair_row, row_pair
 //   4. scatter  one thread per 16-byte chunk of a token row: read x once, write it to each of
 //               the token's local rows                                   -> xp
 //
@@ -23,6 +24,7 @@ namespace probe {
 constexpr int kPermWaves = 4;                 // waves per workgroup in steps 1 and 3
 constexpr int kSegPairs = 256;                // pairs per wave segment
 constexpr int kSegIters = kSegPairs / kWave;  // 4 wave-wide iterations per segment
+constexpr int kRepLds = 2048;                 // replica-list entries staged in LDS by the index kernel
 
 __device__ __forceinline__ uint64_t lanemask_lt() {
   int l = lane_id();
@@ -43,13 +45,12 @@ __device__ __forceinline__ uint64_t match_key8(int key, bool valid) {
 
 // Step 1.
 __global__ __launch_bounds__(kPermWaves* kWave) void permute_hist_kernel(
-    const int32_t* __restrict__ topk_idx, int N, int E, int32_t* __restrict__ seg_hist) {
+    const int32_t* __restrict__ topk_idx, int N, int E, int32_t* __restrict__ blk_hist) {
   __shared__ int32_t cnt_mem[kPermWaves][PROBE_MAX_EXPERTS];
   int w = threadIdx.x / kWave, lane = lane_id();
   volatile int32_t* cnt_w = cnt_mem[w];  // volatile: keep every lane's read before the leader's update
   for (int e = lane; e < E; e += kWave) cnt_w[e] = 0;
-  int seg = blockIdx.x * kPermWaves + w;
-  long base = static_cast<long>(seg) * kSegPairs;
+  long base = (static_cast<long>(blockIdx.x) * kPermWaves + w) * kSegPairs;
   // same-wave LDS accesses execute in program order; no barrier needed for a wave's own row
   for (int it = 0; it < kSegIters; ++it) {
     long p = base + it * kWave + lane;
@@ -58,8 +59,13 @@ __global__ __launch_bounds__(kPermWaves* kWave) void permute_hist_kernel(
     uint64_t m = match_key8(e, valid);
     if (valid && (m & lanemask_lt()) == 0) cnt_w[e] += __popcll(m);
   }
-  if (base < N)
-    for (int e = lane; e < E; e += kWave) seg_hist[static_cast<long>(seg) * E + e] = cnt_w[e];
+  __syncthreads();
+  for (int e = threadIdx.x; e < E; e += kPermWaves * kWave) {
+    int tot = 0;
+#pragma unroll
+    for (int q = 0; q < kPermWaves; ++q) tot += cnt_mem[q][e];
+    blk_hist[static_cast<long>(blockIdx.x) * E + e] = tot;
+  }
 }
 
 // Step 2.  One workgroup of 1024 threads: expert e = tid % 256 is scanned by four threads, each
@@ -170,18 +176,28 @@ __global__ __launch_bounds__(1024) void permute_scan_kernel(
 
 // Step 3.
 __global__ __launch_bounds__(kPermWaves* kWave) void permute_index_kernel(
-    const int32_t* __restrict__ topk_idx, int N, int E, const int32_t* __restrict__ seg_base,
+    const int32_t* __restrict__ topk_idx, int N, int E, const int32_t* __restrict__ blk_base,
     const int32_t* __restrict__ rep_off, const int32_t* __restrict__ rep_slot,
     const int32_t* __restrict__ rep_weight, const int32_t* __restrict__ slot_offsets, int S,
     int32_t* __restrict__ pair_row, int32_t* __restrict__ row_pair) {
   __shared__ int32_t cnt_mem[kPermWaves][PROBE_MAX_EXPERTS];
   __shared__ int32_t e_lo[PROBE_MAX_EXPERTS], e_hi[PROBE_MAX_EXPERTS], e_P[PROBE_MAX_EXPERTS];
   __shared__ int32_t s_off[PROBE_MAX_SLOTS + 1];
+  __shared__ int32_t s_rw[kRepLds], s_rs[kRepLds];
   int w = threadIdx.x / kWave, lane = lane_id();
   volatile int32_t* cnt_w = cnt_mem[w];  // volatile: keep every lane's read before the leader's update
-  int seg = blockIdx.x * kPermWaves + w;
-  long base = static_cast<long>(seg) * kSegPairs;
-  // the plan, once per workgroup: replica range and total weight of every expert, slot offsets
+  long base = (static_cast<long>(blockIdx.x) * kPermWaves + w) * kSegPairs;
+  // the plan, once per workgroup: replica lists (in LDS when they fit), replica range and total
+  // weight of every expert, slot offsets
+  const int R = rep_off[E];
+  const bool staged = R <= kRepLds;
+  if (staged)
+    for (int i = threadIdx.x; i < R; i += kPermWaves * kWave) {
+      s_rw[i] = rep_weight[i];
+      s_rs[i] = rep_slot[i];
+    }
+  const int32_t* rw = staged ? s_rw : rep_weight;  // flat pointers: LDS or global
+  const int32_t* rs = staged ? s_rs : rep_slot;
   for (int e = threadIdx.x; e < E; e += kPermWaves * kWave) {
     int lo = rep_off[e], hi = rep_off[e + 1], P = 0;
     for (int i = lo; i < hi; ++i) P += rep_weight[i];
@@ -190,13 +206,42 @@ __global__ __launch_bounds__(kPermWaves* kWave) void permute_index_kernel(
     e_P[e] = P;
   }
   for (int i = threadIdx.x; i <= S; i += kPermWaves * kWave) s_off[i] = slot_offsets[i];
-  if (base < N)
-    for (int e = lane; e < E; e += kWave) cnt_w[e] = seg_base[static_cast<long>(seg) * E + e];
-  __syncthreads();
-  int n_loc = s_off[S];
+  // counts of this wave's own segment (the same walk as in step 1), kept in registers
+  for (int e = lane; e < E; e += kWave) cnt_w[e] = 0;
+  int seg_e[kSegIters];
+#pragma unroll
   for (int it = 0; it < kSegIters; ++it) {
     long p = base + it * kWave + lane;
     int e = p < N ? topk_idx[p] : -1;
+    seg_e[it] = e;
+    bool valid = static_cast<unsigned>(e) < static_cast<unsigned>(E);
+    uint64_t m = match_key8(e, valid);
+    if (valid && (m & lanemask_lt()) == 0) cnt_w[e] += __popcll(m);
+  }
+  __syncthreads();
+  // arrival rank at the start of this wave's segment: block base + counts of the earlier waves
+  int start[PROBE_MAX_EXPERTS / kWave];
+#pragma unroll
+  for (int i = 0; i < PROBE_MAX_EXPERTS / kWave; ++i) {
+    int e = lane + i * kWave;
+    int v = 0;
+    if (e < E) {
+      v = blk_base[static_cast<long>(blockIdx.x) * E + e];
+      for (int q = 0; q < w; ++q) v += cnt_mem[q][e];
+    }
+    start[i] = v;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < PROBE_MAX_EXPERTS / kWave; ++i) {
+    int e = lane + i * kWave;
+    if (e < E) cnt_w[e] = start[i];
+  }
+  int n_loc = s_off[S];
+#pragma unroll
+  for (int it = 0; it < kSegIters; ++it) {
+    long p = base + it * kWave + lane;
+    int e = seg_e[it];
     bool valid = static_cast<unsigned>(e) < static_cast<unsigned>(E);
     uint64_t m = match_key8(e, valid);
     if (p < N && !valid) {  // expert id out of range: the pair is computed nowhere on this GPU
@@ -211,9 +256,9 @@ __global__ __launch_bounds__(kPermWaves* kWave) void permute_index_kernel(
       if (P > 0) {
         int full = j / P, u = j - full * P, cum = 0;
         for (int i = lo; i < hi; ++i) {
-          int wgt = rep_weight[i];
+          int wgt = rw[i];
           if (u < cum + wgt) {
-            int slot = rep_slot[i];
+            int slot = rs[i];
             if (slot >= 0 && slot < S) row = s_off[slot] + full * wgt + (u - cum);
             if (row >= N) row = -1;  // only an inconsistent plan (two replicas in one slot) gets here
             break;
@@ -254,7 +299,10 @@ __global__ __launch_bounds__(256) void permute_scatter_kernel(const u32x4* __res
     if (rows[s] >= 0) __builtin_nontemporal_store(v, &xp[static_cast<long>(rows[s]) * chunks_per_row + c]);
 }
 
-static int num_segments(long N) { return static_cast<int>((N + kSegPairs - 1) / kSegPairs); }
+static int num_blocks(long N) {
+  const long per = static_cast<long>(kSegPairs) * kPermWaves;
+  return static_cast<int>((N + per - 1) / per);
+}
 
 }  // namespace probe
 
@@ -262,7 +310,7 @@ extern "C" size_t probe_permute_workspace_bytes(int T, int E, int k, int S) {
   (void)S;
   if (T < 0 || E <= 0 || k <= 0) return 0;
   long N = static_cast<long>(T) * k;
-  int U = probe::num_segments(N);
+  int U = probe::num_blocks(N);
   return probe::align_up(static_cast<size_t>(U > 0 ? U : 1) * E * sizeof(int32_t), 256);
 }
 
@@ -294,9 +342,9 @@ extern "C" int probe_permute(const int32_t* topk_idx, const probe_plan* plan, co
                 probe_permute_workspace_bytes(T, E, k, S));
   hipStream_t st = static_cast<hipStream_t>(stream);
   int N = T * k;
-  int U = num_segments(N);
+  int U = num_blocks(N);
   int32_t* seg = static_cast<int32_t*>(workspace);
-  int seg_blocks = (U + kPermWaves - 1) / kPermWaves;
+  int seg_blocks = U;
   if (U > 0)
     hipLaunchKernelGGL(permute_hist_kernel, dim3(seg_blocks), dim3(kPermWaves * kWave), 0, st, topk_idx, N,
                        E, seg);
