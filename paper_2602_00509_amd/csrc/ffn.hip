@@ -25,19 +25,18 @@
 // on the accumulators.  Ragged row counts are handled by clamping the row a lane loads to
 // the slot's last row and masking stores; the row space is never padded.
 #include <mutex>
-#include <type_traits>
 
 #include "common.hpp"
+#include "mfma_pipeline.hpp"
 
 namespace probe {
 
-constexpr int FBN = 256, FBK = 64;
+constexpr int FBN = 256;
 // LDS: the tall tile (256 rows) runs two stages of 64 KB; the short tiles (128 / 64 rows) are bound
 // by load latency rather than by the matrix cores and run three stages of 48 / 40 KB, which
 // gives every DMA batch two k-steps to land.
 constexpr int kFfnLdsBytes = 3 * (128 + 256) * 128;  // 144 KB >= 2 * (256 + 256) * 128
 
-#define PROBE_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 
 // ---- 0. schedule ----------------------------------------------------------------------
 // table[0] = number of tiles; tile i: table[1+3i] = slot, table[2+3i] = first row,
@@ -118,154 +117,6 @@ __global__ __launch_bounds__(256) void ffn_schedule_kernel(const int32_t* __rest
   }
 }
 
-// ---- shared main loop -----------------------------------------------------------------
-// acc += A_tile[64*MI, K] * B_tile[256, K]^T for the calling wave's 32*MI x 64 block.
-// rA / rB are buffer descriptors of the tile's first A row / of the weight matrix; voff[j] is
-// this lane's byte offset for DMA instruction j (AW instructions for A, then 4 for B).
-// NST = LDS stages (2 or 3); a DMA batch is issued NST k-steps ahead of its use.
-template <int N>
-__device__ __forceinline__ void wait_vm_lgkm0() {  // s_waitcnt vmcnt(N) lgkmcnt(0), N < 16
-  __builtin_amdgcn_s_waitcnt(0x0070 | N);
-}
-
-template <int MI, int NST>
-__device__ __forceinline__ void gemm_mainloop(__amdgpu_buffer_rsrc_t rA, __amdgpu_buffer_rsrc_t rB,
-                                              const int (&voff)[MI + 4], int K, u32x4* smem,
-                                              int wv, int lane, f32x16 (&acc)[MI][2]) {
-  constexpr int NI = 2, WN = 4, AW = MI, BW = 4, LPW = AW + BW, BM = 64 * MI;
-  constexpr int kStage = (BM + 256) * 8;  // 16-byte units per stage
-  static_assert(NST == 2 || NST == 3, "two or three stages");
-  static_assert(NST * kStage * 16 <= kFfnLdsBytes, "LDS budget");
-  const int wm = wv / WN, wn = wv % WN;
-
-  auto issue_one = [&](int st, int j, int kbytes) {
-    if (j < AW)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rA, PROBE_LDS_PTR(smem + st * kStage + (wv * AW + j) * 64), 16,
-                                               voff[j], kbytes, 0, 0);
-    else
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(
-          rB, PROBE_LDS_PTR(smem + st * kStage + BM * 8 + (wv * BW + (j - AW)) * 64), 16, voff[j], kbytes, 0, 0);
-  };
-  auto issue_all = [&](int st, int kt) {
-#pragma unroll
-    for (int j = 0; j < LPW; ++j) issue_one(st, j, kt * FBK * 2);
-  };
-  int offA[MI], offB[NI];
-#pragma unroll
-  for (int i = 0; i < MI; ++i) offA[i] = (32 * MI * wm + 32 * i + (lane & 31)) * 8;
-#pragma unroll
-  for (int j = 0; j < NI; ++j) offB[j] = BM * 8 + (64 * wn + 32 * j + (lane & 31)) * 8;
-  const int swz = ((lane & 31) >> 1) & 7;  // (row >> 1) & 7: every 32-row block starts at a multiple of 32
-  auto read_frags = [&](int st, int kk, u32x4(&a)[MI], u32x4(&b)[NI]) {
-    const u32x4* sbase = smem + st * kStage;
-    const int pc = (2 * kk + (lane >> 5)) ^ swz;
-#pragma unroll
-    for (int i = 0; i < MI; ++i) a[i] = sbase[offA[i] + pc];
-#pragma unroll
-    for (int j = 0; j < NI; ++j) b[j] = sbase[offB[j] + pc];
-  };
-  // the weight fragment is the row operand: a lane's accumulator registers 4q..4q+3 are four
-  // consecutive output columns of one output row
-  auto mma = [&](u32x4(&a)[MI], u32x4(&b)[NI]) {
-#pragma unroll
-    for (int i = 0; i < MI; ++i)
-#pragma unroll
-      for (int j = 0; j < NI; ++j) acc[i][j] = mfma_32x32x16(b[j], a[i], acc[i][j]);
-  };
-
-  const int KT = K / FBK;
-  u32x4 a0[MI], b0[NI], a1[MI], b1[NI];
-  // prologue: NST batches in flight, wait for the first
-  issue_all(0, 0);
-  if (KT > 1) issue_all(1, 1);
-  bool waited = false;
-  if constexpr (NST == 3) {
-    if (KT > 2) {
-      issue_all(2, 2);
-      wait_vm_lgkm0<2 * LPW>();
-      waited = true;
-    }
-  }
-  if (!waited) {
-    if (KT > 1) wait_vm_lgkm0<LPW>(); else wait_vm_lgkm0<0>();
-  }
-  __builtin_amdgcn_s_barrier();
-  asm volatile("" ::: "memory");
-  read_frags(0, 0, a0, b0);
-  // One k-step on stage `cur`.  DMA: issue tile kt+NST into the stage being vacated.
-  // YOUNGER: a batch younger than tile kt+1 is in flight at the barrier (it may stay in flight).
-  // NEXT: tile kt+1 exists.
-  auto k_step = [&](int kt, int cur, auto dma_c, auto younger_c, auto next_c) {
-    constexpr bool DMA = decltype(dma_c)::value, YOUNGER = decltype(younger_c)::value,
-                   NEXT = decltype(next_c)::value;
-    const int nxt = (cur + 1 == NST) ? 0 : cur + 1;
-    __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): a0/b0 have arrived
-    read_frags(cur, 1, a1, b1);
-    __builtin_amdgcn_sched_barrier(0);
-    mma(a0, b0);
-    __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_waitcnt(0xC07F);
-    read_frags(cur, 2, a0, b0);
-    __builtin_amdgcn_sched_barrier(0);
-    mma(a1, b1);
-    __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_waitcnt(0xC07F);
-    read_frags(cur, 3, a1, b1);
-    __builtin_amdgcn_sched_barrier(0);
-    mma(a0, b0);
-    __builtin_amdgcn_sched_barrier(0);
-    // every read of stage cur is issued: wait for them and for this wave's share of tile kt+1
-    if constexpr (YOUNGER) wait_vm_lgkm0<LPW>(); else wait_vm_lgkm0<0>();
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-    if constexpr (NEXT) read_frags(nxt, 0, a0, b0);
-    __builtin_amdgcn_sched_barrier(0);
-    if constexpr (DMA) {
-      const int kbytes = (kt + NST) * FBK * 2;
-#pragma unroll
-      for (int t = 0; t < MI * NI; ++t) {
-        acc[t / NI][t % NI] = mfma_32x32x16(b1[t % NI], a1[t / NI], acc[t / NI][t % NI]);
-        if (t < LPW) issue_one(cur, t, kbytes);
-      }
-#pragma unroll
-      for (int t = MI * NI; t < LPW; ++t) issue_one(cur, t, kbytes);
-#pragma unroll
-      for (int t = 0; t < MI * NI; ++t) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
-        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // one VMEM read
-      }
-    } else {
-      mma(a1, b1);
-    }
-  };
-  using T_ = std::integral_constant<bool, true>;
-  using F_ = std::integral_constant<bool, false>;
-  int kt = 0, cur = 0;
-  auto advance = [&]() {
-    ++kt;
-    cur = (cur + 1 == NST) ? 0 : cur + 1;
-  };
-  if constexpr (NST == 2) {
-    for (; kt + 2 < KT; advance()) k_step(kt, cur, T_{}, F_{}, T_{});
-    if (kt + 1 < KT) {
-      k_step(kt, cur, F_{}, F_{}, T_{});
-      advance();
-    }
-  } else {
-    for (; kt + 3 < KT; advance()) k_step(kt, cur, T_{}, T_{}, T_{});
-    if (kt + 2 < KT) {
-      k_step(kt, cur, F_{}, T_{}, T_{});
-      advance();
-    }
-    if (kt + 1 < KT) {
-      k_step(kt, cur, F_{}, F_{}, T_{});
-      advance();
-    }
-  }
-  k_step(kt, cur, F_{}, F_{}, F_{});
-}
-
 template <int MI>
 __device__ __forceinline__ void zero_acc(f32x16 (&acc)[MI][2]) {
 #pragma unroll
@@ -276,22 +127,6 @@ __device__ __forceinline__ void zero_acc(f32x16 (&acc)[MI][2]) {
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 }
 
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, size_t bytes) {
-  unsigned n = bytes > 0xffffffffull ? 0xffffffffu : static_cast<unsigned>(bytes);
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, static_cast<int>(n), 0x00020000);
-}
-
-// Per-lane byte offsets of the DMA instructions of this wave: instruction j covers tile rows
-// (wv*CNT + j)*8 .. +8; lane l reads row +l/8, the chunk that belongs at LDS position l%8.
-template <int CNT, typename RowFn>
-__device__ __forceinline__ void dma_offsets(int wv, int lane, int row_bytes, RowFn row_of, int* out) {
-#pragma unroll
-  for (int j = 0; j < CNT; ++j) {
-    int row = (wv * CNT + j) * 8 + (lane >> 3);
-    int c = (lane & 7) ^ ((row >> 1) & 7);
-    out[j] = row_of(row) * row_bytes + c * 16;
-  }
-}
 
 // ---- workgroup -> (row tile, column block) -----------------------------------------------
 // Workgroups are dealt to the 8 XCDs round-robin by their linear id, and each XCD has its own
@@ -342,7 +177,7 @@ __device__ __forceinline__ void gemm1_tile(const bf16_t* __restrict__ xp, const 
                  voff + MI);
   f32x16 acc[MI][2];
   zero_acc<MI>(acc);
-  gemm_mainloop<MI, (MI == 4 ? 2 : 3)>(rA, rB, voff, H, smem, wv, lane, acc);
+  gemm_mainloop<MI, 2, 1, (MI == 4 ? 2 : 3)>(rA, rB, voff, 0, H, smem, wv, lane, acc);
 
   // The weight fragment is the MFMA's row operand, so accumulator registers 4q..4q+3 of a lane
   // are four consecutive output columns of one output row: one 8-byte store each.
@@ -411,7 +246,7 @@ __device__ __forceinline__ void gemm2_tile(const bf16_t* __restrict__ hbuf, cons
   dma_offsets<4>(wv, lane, F * 2, [&](int j) { return min(n0 + j, H - 1); }, voff + MI);
   f32x16 acc[MI][2];
   zero_acc<MI>(acc);
-  gemm_mainloop<MI, (MI == 4 ? 2 : 3)>(rA, rB, voff, F, smem, wv, lane, acc);
+  gemm_mainloop<MI, 2, 1, (MI == 4 ? 2 : 3)>(rA, rB, voff, 0, F, smem, wv, lane, acc);
 
   const int row_in = 32 * MI * wm + (lane & 31);
 #pragma unroll

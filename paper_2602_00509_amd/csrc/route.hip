@@ -8,14 +8,18 @@
 // fp32, and the MFMA accumulates in fp32.
 //
 //   1. split    w_gate -> planes[3][E][H] bf16 in the workspace; zero the expert counts
-//   2. gemm     split-K tiled GEMM (128 tokens x 128 experts x 64 k per step, 4 waves of
-//               64x64, LDS-staged with register prefetch), three MFMAs per operand pair
-//               (one per plane) into one accumulator               -> partial[KS][T][E] fp32
+//   2. gemm     split-K tiled GEMM (128 tokens x 128 experts x 64 k per step), three MFMAs per
+//               operand pair (one per plane) into one accumulator  -> partial[KS][T][E] fp32
+//               H % 64 == 0: DMA-to-LDS software pipeline shared with the grouped FFN;
+//               otherwise a register-staged kernel that zero-fills the K tail
 //   3. softmax  sixteen lanes per token: sum the KS partials in fixed order, add the bias,
 //               softmax over E, k rounds of row arg-max (ties to the lower index), weights, counts
 #include <limits.h>
 
+#include <mutex>
+
 #include "common.hpp"
+#include "mfma_pipeline.hpp"
 
 namespace probe {
 
@@ -131,6 +135,78 @@ __global__ __launch_bounds__(256, 2) void gate_gemm_kernel(const bf16_t* __restr
         if (row < T && col < E) partial[(static_cast<long>(ks) * T + row) * E + col] = acc[mi][ni][r];
       }
     }
+}
+
+// ---- 2b. gemm, DMA pipeline (H % 64 == 0) --------------------------------------------
+// Same split-K tiling (128 tokens x 128 experts per workgroup), on the software pipeline of the
+// grouped FFN: 8 waves (2 x 4, wave tile 64 tokens x 32 experts), buffer_load-to-LDS, two LDS
+// stages of 64 KB = 128 token rows + 3 planes x 128 expert rows, three MFMAs (one per plane) per
+// operand pair into one accumulator.  The weight fragment is the MFMA's row operand, so a lane
+// ends with four consecutive experts of one token per register quad: 16-byte stores.
+constexpr int kGateLdsBytes = 2 * (128 + 384) * 128;
+
+__global__ __launch_bounds__(512, 2) void gate_gemm_dma_kernel(const bf16_t* __restrict__ x,
+                                                               const bf16_t* __restrict__ planes,
+                                                               int T, int H, int E, int k_chunk,
+                                                               float* __restrict__ partial) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  extern __shared__ u32x4 smem[];
+  const int lane = threadIdx.x & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wv / 4, wn = wv % 4;
+  const int m0 = blockIdx.x * GBM, n0 = blockIdx.y * GBN, ks = blockIdx.z;
+  const int kbeg = ks * k_chunk, klen = min(H, kbeg + k_chunk) - kbeg;
+  if (klen <= 0) return;
+  const int rows = T - m0;
+  __amdgpu_buffer_rsrc_t rA = make_rsrc(x + static_cast<size_t>(m0) * H, static_cast<size_t>(rows) * H * 2);
+  __amdgpu_buffer_rsrc_t rB = make_rsrc(planes, static_cast<size_t>(3) * E * H * 2);
+  int voff[2 + 6];
+  dma_offsets<2>(wv, lane, H * 2, [&](int r) { return min(r, rows - 1); }, voff);
+  // B-tile row j: plane j / 128, expert n0 + j % 128 (clamped; columns past E are masked at the store)
+  dma_offsets<6>(wv, lane, H * 2, [&](int j) { return (j >> 7) * E + min(n0 + (j & 127), E - 1); }, voff + 2);
+  f32x16 acc[2][1];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][0][r] = 0.f;
+  gemm_mainloop<2, 1, 3, 2>(rA, rB, voff, kbeg, klen, smem, wv, lane, acc);
+
+  const bool vec = (E & 3) == 0;
+#pragma unroll
+  for (int mi = 0; mi < 2; ++mi) {
+    const int row = 64 * wm + 32 * mi + (lane & 31);
+    if (row < rows) {
+      float* dst = partial + (static_cast<long>(ks) * T + m0 + row) * E;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int col = n0 + 32 * wn + 8 * q + 4 * (lane >> 5);
+        if (vec) {
+          if (col < E)
+            *reinterpret_cast<float4*>(dst + col) =
+                make_float4(acc[mi][0][4 * q], acc[mi][0][4 * q + 1], acc[mi][0][4 * q + 2], acc[mi][0][4 * q + 3]);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (col + e < E) dst[col + e] = acc[mi][0][4 * q + e];
+        }
+      }
+    }
+  }
+#endif
+}
+
+static int gate_prepare() {
+  static std::once_flag once;
+  static hipError_t err = hipSuccess;
+  std::call_once(once, [] {
+    err = hipFuncSetAttribute(reinterpret_cast<const void*>(gate_gemm_dma_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, kGateLdsBytes);
+  });
+  if (err != hipSuccess) {
+    set_error("probe_route_topk: cannot reserve %d bytes of LDS: %s", kGateLdsBytes, hipGetErrorString(err));
+    return PROBE_EHIP;
+  }
+  return PROBE_OK;
 }
 
 // ---- 3. softmax + top-k ---------------------------------------------------------------
@@ -353,6 +429,10 @@ static int route_impl(const char* name, const void* x_bf16, const float* w_gate,
   PROBE_REQUIRE(workspace && aligned16(workspace) && workspace_bytes >= sh.planes_bytes + sh.partial_bytes,
                 PROBE_EWORKSPACE, "%s: workspace too small or misaligned (%zu < %zu)", name,
                 workspace_bytes, sh.planes_bytes + sh.partial_bytes);
+  if (T > 0 && H % 64 == 0) {
+    int rc = gate_prepare();
+    if (rc != PROBE_OK) return rc;
+  }
   hipStream_t st = static_cast<hipStream_t>(stream);
   bf16_t* planes = static_cast<bf16_t*>(workspace);
   float* partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + sh.planes_bytes);
@@ -362,8 +442,13 @@ static int route_impl(const char* name, const void* x_bf16, const float* w_gate,
   hipLaunchKernelGGL(gate_split_kernel, dim3(static_cast<unsigned>((split_threads + 255) / 256)), dim3(256),
                      0, st, w_gate, n, planes, expert_counts, E);
   if (T > 0) {
-    hipLaunchKernelGGL(gate_gemm_kernel, dim3(sh.mt, sh.nt, sh.ks), dim3(256), 0, st,
-                       static_cast<const bf16_t*>(x_bf16), planes, T, H, E, sh.k_chunk, partial);
+    if (H % 64 == 0) {
+      hipLaunchKernelGGL(gate_gemm_dma_kernel, dim3(sh.mt, sh.nt, sh.ks), dim3(512), kGateLdsBytes, st,
+                         static_cast<const bf16_t*>(x_bf16), planes, T, H, E, sh.k_chunk, partial);
+    } else {
+      hipLaunchKernelGGL(gate_gemm_kernel, dim3(sh.mt, sh.nt, sh.ks), dim3(256), 0, st,
+                         static_cast<const bf16_t*>(x_bf16), planes, T, H, E, sh.k_chunk, partial);
+    }
     int grid = (T + 15) / 16;
     if (grid > 4096) grid = 4096;
     int G = bias ? bias_groups : 1, tpg = bias ? tokens_per_group : 1;
