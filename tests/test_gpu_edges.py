@@ -97,6 +97,23 @@ def test_topk_equals_all_experts_and_predictor_identity(oracle, probe, G):
         assert torch.equal(r[key], pr[key]), key
 
 
+@pytest.mark.parametrize("T,H,E,k", [(150, 72, 20, 3), (300, 200, 130, 8), (64, 8, 5, 2), (129, 1000, 256, 8)])
+def test_route_when_hidden_size_is_not_a_multiple_of_64(oracle, probe, G, T, H, E, k):
+    """H % 8 == 0 is all the router asks for; these shapes take the kernel that zero-fills the K tail."""
+    print("case route H=%d" % H, flush=True)
+    rng = np.random.default_rng(H)
+    x = wl.f32_to_bf16_bits(rng.standard_normal((T, H), dtype=np.float32))
+    wg = (rng.standard_normal((E, H), dtype=np.float32) * np.float32(0.05))
+    b = rng.standard_normal((2, E)).astype(np.float32)
+    tpg = 100
+    g = probe.route_topk(G.dev_bf16(x), torch.from_numpy(wg).cuda(), torch.from_numpy(b).cuda(), tpg, k, True,
+                         want_probs=True)
+    torch.cuda.synchronize()
+    o = oracle.route_topk(x, wg, b, tpg, k, True)
+    G.check_route(g, o, k, True)
+    np.testing.assert_array_equal(g["counts"].cpu().numpy(), np.bincount(g["idx"].cpu().numpy().ravel(), minlength=E))
+
+
 def test_determinism_and_plan_invariance(oracle, probe, G):
     """Two runs are bit-identical; with every replica local, any plan gives the same layer output."""
     print("case determinism / plan invariance", flush=True)
