@@ -307,21 +307,27 @@ static FfnShape ffn_shape(int S, int F, int max_rows) {
   return s;
 }
 
-// The GEMM kernels use 128 KB of dynamic LDS, which has to be opted into once per process.
+// The GEMM kernels use 144 KB of dynamic LDS, which has to be opted into once per device.
 static int ffn_prepare() {
-  static std::once_flag once;
-  static hipError_t err = hipSuccess;
-  std::call_once(once, [] {
-    err = hipFuncSetAttribute(reinterpret_cast<const void*>(ffn_gemm1_kernel),
+  static std::mutex mu;
+  static bool done[64] = {false};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+    set_error("probe_grouped_ffn: no current device");
+    return PROBE_EHIP;
+  }
+  std::lock_guard<std::mutex> lock(mu);
+  if (done[dev]) return PROBE_OK;
+  hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(ffn_gemm1_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kFfnLdsBytes);
+  if (err == hipSuccess)
+    err = hipFuncSetAttribute(reinterpret_cast<const void*>(ffn_gemm2_kernel),
                               hipFuncAttributeMaxDynamicSharedMemorySize, kFfnLdsBytes);
-    if (err == hipSuccess)
-      err = hipFuncSetAttribute(reinterpret_cast<const void*>(ffn_gemm2_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kFfnLdsBytes);
-  });
   if (err != hipSuccess) {
     set_error("probe_grouped_ffn: cannot reserve %d bytes of LDS: %s", kFfnLdsBytes, hipGetErrorString(err));
     return PROBE_EHIP;
   }
+  done[dev] = true;
   return PROBE_OK;
 }
 
@@ -344,8 +350,8 @@ extern "C" int probe_grouped_ffn(const void* xp_bf16, const int32_t* slot_offset
   PROBE_REQUIRE(S <= PROBE_MAX_SLOTS && H % 64 == 0 && F % 64 == 0, PROBE_EUNSUPPORTED,
                 "probe_grouped_ffn: needs S <= %d, H %% 64 == 0, F %% 64 == 0 (S=%d H=%d F=%d)",
                 PROBE_MAX_SLOTS, S, H, F);
-  PROBE_REQUIRE(static_cast<size_t>(2) * F * H * 2 <= 0xffffffffull, PROBE_EUNSUPPORTED,
-                "probe_grouped_ffn: one expert's w13 must stay below 4 GiB (H=%d F=%d)", H, F);
+  PROBE_REQUIRE(static_cast<size_t>(2) * F * H * 2 <= 0x7fffffffull, PROBE_EUNSUPPORTED,
+                "probe_grouped_ffn: one expert's w13 must stay below 2 GiB (H=%d F=%d)", H, F);
   if (max_rows == 0) return PROBE_OK;
   PROBE_REQUIRE(xp_bf16 && slot_offsets && w13_ptrs && w2_ptrs && y_bf16, PROBE_EINVAL,
                 "probe_grouped_ffn: null pointer");

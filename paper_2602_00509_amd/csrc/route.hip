@@ -196,16 +196,22 @@ __global__ __launch_bounds__(512, 2) void gate_gemm_dma_kernel(const bf16_t* __r
 }
 
 static int gate_prepare() {
-  static std::once_flag once;
-  static hipError_t err = hipSuccess;
-  std::call_once(once, [] {
-    err = hipFuncSetAttribute(reinterpret_cast<const void*>(gate_gemm_dma_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, kGateLdsBytes);
-  });
+  static std::mutex mu;
+  static bool done[64] = {false};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+    set_error("probe_route_topk: no current device");
+    return PROBE_EHIP;
+  }
+  std::lock_guard<std::mutex> lock(mu);
+  if (done[dev]) return PROBE_OK;
+  hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(gate_gemm_dma_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kGateLdsBytes);
   if (err != hipSuccess) {
     set_error("probe_route_topk: cannot reserve %d bytes of LDS: %s", kGateLdsBytes, hipGetErrorString(err));
     return PROBE_EHIP;
   }
+  done[dev] = true;
   return PROBE_OK;
 }
 
@@ -246,142 +252,195 @@ __device__ __forceinline__ void argmax_step(float& v, int& e) {
   e = take ? oe : e;
 }
 
+__device__ __forceinline__ int row_min_i(int v) {
+  v = min(v, dpp_ror<8>(v));
+  v = min(v, dpp_ror<4>(v));
+  v = min(v, dpp_ror<2>(v));
+  v = min(v, dpp_ror<1>(v));
+  return v;
+}
+
+// Two tokens per row are in flight (U = 2) so that the dependent DPP chains of one overlap the
+// other's.  A chosen logit is overwritten with -inf; incoming logits are clamped to >= -FLT_MAX
+// (NaN too), so -inf only ever means "taken".  The weight of a winner is recomputed from its
+// logit with the same expression as its probability, so both agree bit for bit.
 template <int NV>
 __global__ __launch_bounds__(256) void gate_softmax_topk_kernel(
     const float* __restrict__ partial, int KS, const float* __restrict__ bias, int G, int tpg, int T,
     int E, int k, int renorm, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
     float* __restrict__ probs, int32_t* __restrict__ counts) {
+  constexpr int U = 2, NL = NV * 4;
   __shared__ int32_t hist[PROBE_MAX_EXPERTS];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int sub = lane & 15, grp = lane >> 4;
   hist[tid] = 0;
   __syncthreads();
-  const float ninf = -__builtin_inff();
+  const float ninf = -__builtin_inff(), fmin_ = -3.402823466e38f;
   const bool vec = (E & 3) == 0;
-  const int tokens_per_pass = gridDim.x * 16;
-  for (int t = (blockIdx.x * 4 + wv) * 4 + grp; t < T + 3; t += tokens_per_pass) {
-    // the four rows of a wave run in lock step; rows past T compute on a clamped token and skip stores
-    const bool live = t < T;
-    const int tt = live ? t : T - 1;
-    int g = 0;
-    if (bias) g = min(tt / tpg, G - 1);
-    float l[NV * 4], p[NV * 4];
+  const int tokens_per_pass = gridDim.x * 16 * U;
+  for (int t0 = ((blockIdx.x * 4 + wv) * U) * 4 + grp; t0 < T; t0 += tokens_per_pass) {
+    // token u of this row is t0 + 4u; the rows of a wave are independent under DPP row operations
+    int tt[U];
+    bool live[U];
+    float l[U][NL];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      live[u] = t0 + 4 * u < T;
+      tt[u] = live[u] ? t0 + 4 * u : t0;
+    }
     if (vec) {
-      // all loads of a round of four split-K slices are issued before any is consumed
-      float4 accv[NV];
+      float4 accv[U][NV];
 #pragma unroll
-      for (int i = 0; i < NV; ++i) accv[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-      for (int q0 = 0; q0 < KS; q0 += 4) {
-        float4 tmp[4][NV];
+      for (int u = 0; u < U; ++u)
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int q = min(q0 + u, KS - 1);
+        for (int i = 0; i < NV; ++i) accv[u][i] = make_float4(0.f, 0.f, 0.f, 0.f);
+      for (int q0 = 0; q0 < KS; q0 += 2) {
+        // all loads of a round of two split-K slices (of both tokens) are issued before any is consumed
+        float4 tmp[2][U][NV];
 #pragma unroll
-          for (int i = 0; i < NV; ++i) {
-            const int e0 = min(64 * i + 4 * sub, E - 4);
-            tmp[u][i] = *reinterpret_cast<const float4*>(partial + (static_cast<long>(q) * T + tt) * E + e0);
-          }
-        }
+        for (int r = 0; r < 2; ++r) {
+          const int q = min(q0 + r, KS - 1);
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
-          if (q0 + u < KS) {
+          for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int i = 0; i < NV; ++i) {
-              accv[i].x += tmp[u][i].x; accv[i].y += tmp[u][i].y;
-              accv[i].z += tmp[u][i].z; accv[i].w += tmp[u][i].w;
+              const int e0 = min(64 * i + 4 * sub, E - 4);
+              tmp[r][u][i] = *reinterpret_cast<const float4*>(partial + (static_cast<long>(q) * T + tt[u]) * E + e0);
             }
+        }
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+          if (q0 + r < KS) {
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+              for (int i = 0; i < NV; ++i) {
+                accv[u][i].x += tmp[r][u][i].x; accv[u][i].y += tmp[r][u][i].y;
+                accv[u][i].z += tmp[r][u][i].z; accv[u][i].w += tmp[r][u][i].w;
+              }
           }
       }
 #pragma unroll
-      for (int i = 0; i < NV; ++i) {
-        const int e0 = 64 * i + 4 * sub;
-        float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (bias && e0 < E) bv = *reinterpret_cast<const float4*>(bias + static_cast<long>(g) * E + e0);
-        l[4 * i] = (e0 < E) ? accv[i].x + bv.x : ninf;
-        l[4 * i + 1] = (e0 < E) ? accv[i].y + bv.y : ninf;
-        l[4 * i + 2] = (e0 < E) ? accv[i].z + bv.z : ninf;
-        l[4 * i + 3] = (e0 < E) ? accv[i].w + bv.w : ninf;
+      for (int u = 0; u < U; ++u) {
+        int g = 0;
+        if (bias) g = min(tt[u] / tpg, G - 1);
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+          const int e0 = 64 * i + 4 * sub;
+          float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (bias && e0 < E) bv = *reinterpret_cast<const float4*>(bias + static_cast<long>(g) * E + e0);
+          l[u][4 * i] = accv[u][i].x + bv.x;
+          l[u][4 * i + 1] = accv[u][i].y + bv.y;
+          l[u][4 * i + 2] = accv[u][i].z + bv.z;
+          l[u][4 * i + 3] = accv[u][i].w + bv.w;
+        }
       }
     } else {
 #pragma unroll
-      for (int i = 0; i < NV; ++i)
+      for (int u = 0; u < U; ++u) {
+        int g = 0;
+        if (bias) g = min(tt[u] / tpg, G - 1);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int e = 64 * i + 4 * sub + j;
+        for (int i = 0; i < NL; ++i) {
+          const int e = 64 * (i >> 2) + 4 * sub + (i & 3);
           float sacc = 0.f;
           if (e < E) {
-            for (int q = 0; q < KS; ++q) sacc += partial[(static_cast<long>(q) * T + tt) * E + e];
+            for (int q = 0; q < KS; ++q) sacc += partial[(static_cast<long>(q) * T + tt[u]) * E + e];
             if (bias) sacc += bias[static_cast<long>(g) * E + e];
           }
-          l[4 * i + j] = (e < E) ? sacc : ninf;
-        }
-    }
-    float mx = l[0];
-#pragma unroll
-    for (int i = 1; i < NV * 4; ++i) mx = fmaxf(mx, l[i]);
-    mx = row_max(mx);
-    float sum = 0.f;
-#pragma unroll
-    for (int i = 0; i < NV * 4; ++i) {
-      p[i] = (l[i] == ninf) ? 0.f : expf(l[i] - mx);
-      sum += p[i];
-    }
-    sum = row_sum(sum);
-    const float inv = 1.f / sum;
-#pragma unroll
-    for (int i = 0; i < NV * 4; ++i) p[i] *= inv;
-    if (probs && live) {
-#pragma unroll
-      for (int i = 0; i < NV; ++i) {
-        const int e0 = 64 * i + 4 * sub;
-        if (vec) {
-          if (e0 < E)
-            *reinterpret_cast<float4*>(probs + static_cast<long>(t) * E + e0) =
-                make_float4(p[4 * i], p[4 * i + 1], p[4 * i + 2], p[4 * i + 3]);
-        } else {
-#pragma unroll
-          for (int j = 0; j < 4; ++j)
-            if (e0 + j < E) probs[static_cast<long>(t) * E + e0 + j] = p[4 * i + j];
+          l[u][i] = sacc;
         }
       }
     }
-    unsigned taken = 0;
-    int isel = 0;
-    float wsel = 0.f, wtot = 0.f;
-    for (int s = 0; s < k; ++s) {
-      float bv = ninf, bp = 0.f;
-      int be = INT_MAX;
+    float mx[U], inv[U];
 #pragma unroll
-      for (int i = 0; i < NV * 4; ++i) {
+    for (int u = 0; u < U; ++u) {
+      // clamp (NaN and -inf become the most negative finite value); experts past E are "taken"
+#pragma unroll
+      for (int i = 0; i < NL; ++i) {
         const int e = 64 * (i >> 2) + 4 * sub + (i & 3);
-        const bool ok = e < E && !((taken >> i) & 1u) && (be == INT_MAX || l[i] > bv);
-        bv = ok ? l[i] : bv;
-        bp = ok ? p[i] : bp;
-        be = ok ? e : be;
+        float v = l[u][i];
+        v = (v >= fmin_) ? v : fmin_;
+        l[u][i] = (e < E) ? v : ninf;
       }
-      const int mine = be;  // this lane's candidate
-      argmax_step<8>(bv, be);
-      argmax_step<4>(bv, be);
-      argmax_step<2>(bv, be);
-      argmax_step<1>(bv, be);
-      // the winner's probability: only its owner contributes, the row sum broadcasts it
-      const bool owner = (mine == be);
-      const float pw = row_sum(owner ? bp : 0.f);
-      if (owner) {
-        const int i = ((be >> 6) << 2) | (be & 3);
-        taken |= 1u << i;
+      float m = l[u][0];
+#pragma unroll
+      for (int i = 1; i < NL; ++i) m = fmaxf(m, l[u][i]);
+      mx[u] = row_max(m);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float p[NL], sum = 0.f;
+#pragma unroll
+      for (int i = 0; i < NL; ++i) {
+        p[i] = expf(l[u][i] - mx[u]);  // exp(-inf) = 0 for the experts past E
+        sum += p[i];
       }
-      wtot += pw;
-      if (sub == s) {
-        isel = be;
-        wsel = pw;
+      sum = row_sum(sum);
+      inv[u] = 1.f / sum;
+      if (probs && live[u]) {
+        const long t = t0 + 4 * u;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+          const int e0 = 64 * i + 4 * sub;
+          if (vec) {
+            if (e0 < E)
+              *reinterpret_cast<float4*>(probs + t * E + e0) =
+                  make_float4(p[4 * i] * inv[u], p[4 * i + 1] * inv[u], p[4 * i + 2] * inv[u], p[4 * i + 3] * inv[u]);
+          } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+              if (e0 + j < E) probs[t * E + e0 + j] = p[4 * i + j] * inv[u];
+          }
+        }
       }
     }
-    if (renorm) wsel /= wtot;
-    if (live && sub < k) {
-      topk_idx[static_cast<long>(t) * k + sub] = isel;
-      topk_w[static_cast<long>(t) * k + sub] = wsel;
-      if (counts) atomicAdd(&hist[isel], 1);
+    int isel[U];
+    float wsel[U], wtot[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      isel[u] = 0;
+      wsel[u] = 0.f;
+      wtot[u] = 0.f;
+    }
+    for (int s = 0; s < k; ++s) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        float m = l[u][0];
+#pragma unroll
+        for (int i = 1; i < NL; ++i) m = fmaxf(m, l[u][i]);
+        const float best = row_max(m);
+        // lowest expert id among the entries that hold the row maximum
+        int cand = INT_MAX;
+#pragma unroll
+        for (int i = NL - 1; i >= 0; --i) {
+          const int e = 64 * (i >> 2) + 4 * sub + (i & 3);
+          cand = (l[u][i] == best) ? e : cand;
+        }
+        const int be = row_min_i(cand);
+        // its owner marks it taken
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+          const int e = 64 * (i >> 2) + 4 * sub + (i & 3);
+          l[u][i] = (e == be) ? ninf : l[u][i];
+        }
+        const float pw = expf(best - mx[u]) * inv[u];
+        wtot[u] += pw;
+        if (sub == s) {
+          isel[u] = be;
+          wsel[u] = pw;
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (renorm) wsel[u] /= wtot[u];
+      if (live[u] && sub < k) {
+        const long t = t0 + 4 * u;
+        topk_idx[t * k + sub] = isel[u];
+        topk_w[t * k + sub] = wsel[u];
+        if (counts) atomicAdd(&hist[isel[u]], 1);
+      }
     }
   }
   __syncthreads();
@@ -429,7 +488,7 @@ static int route_impl(const char* name, const void* x_bf16, const float* w_gate,
   PROBE_REQUIRE(workspace && aligned16(workspace) && workspace_bytes >= sh.planes_bytes + sh.partial_bytes,
                 PROBE_EWORKSPACE, "%s: workspace too small or misaligned (%zu < %zu)", name,
                 workspace_bytes, sh.planes_bytes + sh.partial_bytes);
-  if (T > 0 && H % 64 == 0) {
+  if (T > 0 && H % 64 == 0 && static_cast<size_t>(3) * E * H * 2 <= 0x7fffffffull) {
     int rc = gate_prepare();
     if (rc != PROBE_OK) return rc;
   }
@@ -442,14 +501,14 @@ static int route_impl(const char* name, const void* x_bf16, const float* w_gate,
   hipLaunchKernelGGL(gate_split_kernel, dim3(static_cast<unsigned>((split_threads + 255) / 256)), dim3(256),
                      0, st, w_gate, n, planes, expert_counts, E);
   if (T > 0) {
-    if (H % 64 == 0) {
+    if (H % 64 == 0 && static_cast<size_t>(3) * E * H * 2 <= 0x7fffffffull) {
       hipLaunchKernelGGL(gate_gemm_dma_kernel, dim3(sh.mt, sh.nt, sh.ks), dim3(512), kGateLdsBytes, st,
                          static_cast<const bf16_t*>(x_bf16), planes, T, H, E, sh.k_chunk, partial);
     } else {
       hipLaunchKernelGGL(gate_gemm_kernel, dim3(sh.mt, sh.nt, sh.ks), dim3(256), 0, st,
                          static_cast<const bf16_t*>(x_bf16), planes, T, H, E, sh.k_chunk, partial);
     }
-    int grid = (T + 15) / 16;
+    int grid = (T + 31) / 32;
     if (grid > 4096) grid = 4096;
     int G = bias ? bias_groups : 1, tpg = bias ? tokens_per_group : 1;
 #define PROBE_TOPK_LAUNCH(V)                                                                           \
