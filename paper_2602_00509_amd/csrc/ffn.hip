@@ -8,12 +8,12 @@
 // the 8-consecutive-k-per-lane operand layout of v_mfma_f32_32x32x16_bf16, so an MFMA operand
 // is one 16-byte LDS read.
 //
-// One workgroup = 8 waves (2 x 4) computes a 256 x 256 output tile (128 x 256 or 64 x 256 for the
-// ragged remainder of a slot) in steps of 64 k:
+// One workgroup = 8 waves (2 x 4) computes a 256 x 256 output tile (320, 192, 128 or 64 rows x 256
+// where a slot's row count is not a multiple of 256) in steps of 64 k:
 //   * global -> LDS goes through buffer_load ... lds (no register staging).  The per-lane
 //     offset is fixed for the whole K loop; the k position travels in a scalar offset.
-//   * two LDS stages of 64 KB (three smaller ones for the short tiles).  Rows are 128 bytes; 16-byte chunk c of row r is stored at chunk
-//     position c ^ ((r >> 1) & 7), which makes sixteen consecutive rows reading the same
+//   * two LDS stages of up to 72 KB (three smaller ones for the 128- and 64-row tiles).  Rows are
+//     128 bytes; 16-byte chunk c of row r is stored at chunk position c ^ ((r >> 1) & 7), which makes sixteen consecutive rows reading the same
 //     logical chunk cover all 64 banks exactly once.
 //   * per k-step a wave runs four groups of MFMAs; the fragments of group g+1 are read from LDS
 //     while group g executes.  The workgroup barrier sits before the last group, whose MFMAs
@@ -32,86 +32,131 @@
 namespace probe {
 
 constexpr int FBN = 256;
-// LDS: the tall tile (256 rows) runs two stages of 64 KB; the short tiles (128 / 64 rows) are bound
-// by load latency rather than by the matrix cores and run three stages of 48 / 40 KB, which
-// gives every DMA batch two k-steps to land.
-constexpr int kFfnLdsBytes = 3 * (128 + 256) * 128;  // 144 KB >= 2 * (256 + 256) * 128
+// LDS: tiles of 192 rows and more run two stages (72 KB each for the 320-row tile); the short
+// tiles (128 / 64 rows) are bound by load latency rather than by the matrix cores and run three
+// stages of 48 / 40 KB, which gives every DMA batch two k-steps to land.
+constexpr int kFfnLdsBytes = 3 * (128 + 256) * 128;  // 144 KB
+static_assert(kFfnLdsBytes >= 2 * (320 + 256) * 128, "two stages of the tallest tile");
 
 
 // ---- 0. schedule ----------------------------------------------------------------------
 // table[0] = number of tiles; tile i: table[1+3i] = slot, table[2+3i] = first row,
-// table[3+3i] = tile height (256, 128 or 64).  A slot of M rows gets floor(M/256) tall tiles
-// and, for the remainder r, one more tile of the smallest height that holds r.  Tiles are
-// listed tallest first (all 256-row tiles, then the 128s, then the 64s), so that the long
-// workgroups start early and the short ones fill the tail of the launch.
-__device__ __forceinline__ int tiles_of_class(int m, int cls) {
-  const int r = m & 255;
-  if (cls == 0) return (m >> 8) + (r > 128 ? 1 : 0);
-  if (cls == 1) return (r > 64 && r <= 128) ? 1 : 0;
-  return (r > 0 && r <= 64) ? 1 : 0;
+// table[3+3i] = tile height (320, 256, 192, 128 or 64).
+//
+// How a slot is cut.  Every tile streams 256 weight rows per k-step whatever its height, so a
+// short tile costs far more than its share of rows (64 rows take about 0.6 of the time of 256) and
+// the 320-row tile is the cheapest per row.  A slot of M rows, u = ceil(M / 64), becomes a tiles of
+// 320 and b tiles of 256 with 5a + 4b = u and a as large as possible: b = 4u mod 5, which exists
+// whenever 4b <= u (every u >= 12).  The six values of u without such a cut get one short tile:
+//   u = 1, 2, 3: one tile of 64u rows;  6: 192 + 192;  7: 256 + 192;  11: 256 + 256 + 192.
+// Inside a slot the 320s come first, then the 256s, then the 192s.
+//
+// Order of the table.  Slots are taken by descending row count (ties: lower slot first) and a
+// slot's tiles stay together: the workgroups that run side by side then share a slot's weight
+// slices in L2, the long slots start early and the single short tiles fill the tail of the launch.
+struct SlotCut {
+  int n320, n256, n192, tail;  // tail = height of the single 64/128/192-row tile when u <= 3, else 0
+  __device__ __forceinline__ int tiles() const { return n320 + n256 + n192 + (tail ? 1 : 0); }
+};
+
+__device__ __forceinline__ SlotCut cut_slot(int m) {
+  SlotCut c = {0, 0, 0, 0};
+  const int u = (m + 63) >> 6;
+  if (u == 0) return c;
+  if (u <= 3) {
+    c.tail = 64 * u;
+    return c;
+  }
+  const int b = (4 * u) % 5;
+  if (4 * b <= u) {
+    c.n256 = b;
+    c.n320 = (u - 4 * b) / 5;
+  } else if (u == 6) {
+    c.n192 = 2;
+  } else {  // u == 7 or u == 11
+    c.n256 = u == 7 ? 1 : 2;
+    c.n192 = 1;
+  }
+  return c;
 }
 
 __global__ __launch_bounds__(256) void ffn_schedule_kernel(const int32_t* __restrict__ slot_offsets,
                                                            int S, int max_tiles,
                                                            int32_t* __restrict__ table) {
-  __shared__ int32_t start[3][PROBE_MAX_SLOTS + 1];  // exclusive prefix of tiles per class
+  __shared__ int32_t rows_of[PROBE_MAX_SLOTS];
+  __shared__ int32_t slot_at[PROBE_MAX_SLOTS];       // slot at each position of the sorted order
+  __shared__ int32_t start[PROBE_MAX_SLOTS + 1];     // first tile of each position (exclusive prefix)
   __shared__ int32_t wave_tot[4];
   const int tid = threadIdx.x, lane = tid & 63;
   int m[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    int s = tid * 4 + i;
+    const int s = tid * 4 + i;
     m[i] = (s < S) ? max(slot_offsets[s + 1] - slot_offsets[s], 0) : 0;
-  }
-  for (int cls = 0; cls < 3; ++cls) {
-    int v[4], local = 0;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      v[i] = tiles_of_class(m[i], cls);
-      local += v[i];
-    }
-    int incl = local;
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-      int o = __shfl_up(incl, d, kWave);
-      if (lane >= d) incl += o;
-    }
-    __syncthreads();  // wave_tot of the previous class has been consumed
-    if (lane == kWave - 1) wave_tot[tid >> 6] = incl;
-    __syncthreads();
-    int excl = incl - local;
-    for (int i = 0; i < (tid >> 6); ++i) excl += wave_tot[i];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      int s = tid * 4 + i;
-      if (s < S) start[cls][s] = excl;
-      excl += v[i];
-    }
-    if (tid == 255) start[cls][S] = excl;  // the last thread's running sum is the class total
+    if (s < S) rows_of[s] = m[i];
   }
   __syncthreads();
-  const int n0 = start[0][S], n1 = start[1][S], n2 = start[2][S];
-  const int total = min(n0 + n1 + n2, max_tiles);
+  // position of a slot = number of slots that come before it
+  int pos[4] = {0, 0, 0, 0};
+  for (int u = 0; u < S; ++u) {
+    const int ru = rows_of[u];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) pos[i] += (ru > m[i] || (ru == m[i] && u < tid * 4 + i)) ? 1 : 0;
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    if (tid * 4 + i < S) slot_at[pos[i]] = tid * 4 + i;
+  __syncthreads();
+  // exclusive prefix of tiles over positions tid*4 .. tid*4+3
+  int v[4], local = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int p = tid * 4 + i;
+    v[i] = p < S ? cut_slot(rows_of[slot_at[p]]).tiles() : 0;
+    local += v[i];
+  }
+  int incl = local;
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    int o = __shfl_up(incl, d, kWave);
+    if (lane >= d) incl += o;
+  }
+  if (lane == kWave - 1) wave_tot[tid >> 6] = incl;
+  __syncthreads();
+  int excl = incl - local;
+  for (int i = 0; i < (tid >> 6); ++i) excl += wave_tot[i];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int p = tid * 4 + i;
+    if (p < S) start[p] = excl;
+    excl += v[i];
+  }
+  if (tid == 255) start[S] = excl;  // the last thread's running sum is the total
+  __syncthreads();
+  const int total = min(start[S], max_tiles);
   if (tid == 0) table[0] = total;
   for (int t = tid; t < total; t += 256) {
-    const int cls = t < n0 ? 0 : (t < n0 + n1 ? 1 : 2);
-    const int r = t - (cls == 0 ? 0 : (cls == 1 ? n0 : n0 + n1));
-    const int32_t* st = start[cls];
-    int lo = 0, hi = S;  // last slot with st[slot] <= r
+    int lo = 0, hi = S;  // last position with start[position] <= t
     while (hi - lo > 1) {
       int mid = (lo + hi) >> 1;
-      if (st[mid] <= r) lo = mid; else hi = mid;
+      if (start[mid] <= t) lo = mid; else hi = mid;
     }
-    const int first = slot_offsets[lo], rows = slot_offsets[lo + 1] - first;
-    int row0, height;
-    if (cls == 0) {
-      row0 = first + (r - st[lo]) * 256;
+    const int slot = slot_at[lo], first = slot_offsets[slot];
+    const SlotCut c = cut_slot(rows_of[slot]);
+    int i = t - start[lo], row0 = first, height;
+    if (i < c.n320) {
+      row0 += i * 320;
+      height = 320;
+    } else if ((i -= c.n320) < c.n256) {
+      row0 += c.n320 * 320 + i * 256;
       height = 256;
+    } else if ((i -= c.n256) < c.n192) {
+      row0 += c.n320 * 320 + c.n256 * 256 + i * 192;
+      height = 192;
     } else {
-      row0 = first + (rows & ~255);  // the remainder starts after the full tall tiles
-      height = cls == 1 ? 128 : 64;
+      height = c.tail;
     }
-    table[1 + 3 * t] = lo;
+    table[1 + 3 * t] = slot;
     table[2 + 3 * t] = row0;
     table[3 + 3 * t] = height;
   }
@@ -177,7 +222,7 @@ __device__ __forceinline__ void gemm1_tile(const bf16_t* __restrict__ xp, const 
                  voff + MI);
   f32x16 acc[MI][2];
   zero_acc<MI>(acc);
-  gemm_mainloop<MI, 2, 1, (MI == 4 ? 2 : 3)>(rA, rB, voff, 0, H, smem, wv, lane, acc);
+  gemm_mainloop<MI, 2, 1, (MI >= 3 ? 2 : 3)>(rA, rB, voff, 0, H, smem, wv, lane, acc);
 
   // The weight fragment is the MFMA's row operand, so accumulator registers 4q..4q+3 of a lane
   // are four consecutive output columns of one output row: one 8-byte store each.
@@ -221,8 +266,12 @@ __global__ __launch_bounds__(512, 2) void ffn_gemm1_kernel(const bf16_t* __restr
   const int row_end = slot_offsets[slot + 1];
   const int n0 = col * 128;
   const bf16_t* w13 = static_cast<const bf16_t*>(w13_ptrs[slot]);
-  if (height > 128)
+  if (height > 256)
+    gemm1_tile<5>(xp, w13, row0, row_end, n0, H, F, hbuf, smem);
+  else if (height > 192)
     gemm1_tile<4>(xp, w13, row0, row_end, n0, H, F, hbuf, smem);
+  else if (height > 128)
+    gemm1_tile<3>(xp, w13, row0, row_end, n0, H, F, hbuf, smem);
   else if (height > 64)
     gemm1_tile<2>(xp, w13, row0, row_end, n0, H, F, hbuf, smem);
   else
@@ -246,7 +295,7 @@ __device__ __forceinline__ void gemm2_tile(const bf16_t* __restrict__ hbuf, cons
   dma_offsets<4>(wv, lane, F * 2, [&](int j) { return min(n0 + j, H - 1); }, voff + MI);
   f32x16 acc[MI][2];
   zero_acc<MI>(acc);
-  gemm_mainloop<MI, 2, 1, (MI == 4 ? 2 : 3)>(rA, rB, voff, 0, F, smem, wv, lane, acc);
+  gemm_mainloop<MI, 2, 1, (MI >= 3 ? 2 : 3)>(rA, rB, voff, 0, F, smem, wv, lane, acc);
 
   const int row_in = 32 * MI * wm + (lane & 31);
 #pragma unroll
@@ -285,8 +334,12 @@ __global__ __launch_bounds__(512, 2) void ffn_gemm2_kernel(const bf16_t* __restr
   const int row_end = slot_offsets[slot + 1];
   const int n0 = col * FBN;
   const bf16_t* w2 = static_cast<const bf16_t*>(w2_ptrs[slot]);
-  if (height > 128)
+  if (height > 256)
+    gemm2_tile<5>(hbuf, w2, row0, row_end, n0, H, F, y, smem);
+  else if (height > 192)
     gemm2_tile<4>(hbuf, w2, row0, row_end, n0, H, F, y, smem);
+  else if (height > 128)
+    gemm2_tile<3>(hbuf, w2, row0, row_end, n0, H, F, y, smem);
   else if (height > 64)
     gemm2_tile<2>(hbuf, w2, row0, row_end, n0, H, F, y, smem);
   else

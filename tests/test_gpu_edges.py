@@ -215,3 +215,28 @@ def test_graph_replay(oracle, probe, G):
         torch.cuda.synchronize()
         assert torch.equal(bufs["r"]["idx"], ref_idx) and torch.equal(bufs["p"]["row_pair"], ref_rows), i
         assert torch.equal(bufs["y"][:nl], ref["y"][:nl]) and torch.equal(bufs["out"], ref["out"]), i
+
+
+def test_ffn_every_way_a_slot_is_cut_into_tiles(oracle, probe, G):
+    """Slot sizes on both sides of every tile-height boundary (the FFN cuts a slot into row tiles of
+    several heights and lets taller tiles absorb small remainders), empty slots in between: every
+    output element against the oracle."""
+    cfg = wl.small_config(T=64, H=128, E=4, k=2, F=192, cid=93)
+    sizes = [0, 1, 63, 64, 65, 128, 129, 191, 192, 193, 255, 256, 257, 0, 300, 320, 321, 384, 385, 449,
+             512, 513, 576, 577, 640, 641, 700, 768 + 1, 768 + 65, 768 + 129, 768 + 192, 768 + 193, 1024 + 130, 7]
+    S = len(sizes)
+    so = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    n = int(so[-1])
+    ws = wl.expert_weights_many(cfg, [s % 4 for s in range(S)])
+    rng = np.random.default_rng(5)
+    xp = wl.f32_to_bf16_bits(rng.standard_normal((n + 9, cfg.H)).astype(np.float32))
+    d_w = {e: (G.dev_bf16(ws[e][0]), G.dev_bf16(ws[e][1])) for e in range(4)}
+    tab = probe.WeightTable([d_w[s % 4][0] for s in range(S)], [d_w[s % 4][1] for s in range(S)])
+    d_xp = G.dev_bf16(xp)
+    y = torch.full((n + 9, cfg.H), 7.0, dtype=torch.bfloat16, device="cuda")
+    probe.grouped_ffn(d_xp, torch.from_numpy(so).cuda(), tab, out=y)
+    torch.cuda.synchronize()
+    ref = oracle.grouped_ffn(xp, so, [ws[s % 4][0] for s in range(S)], [ws[s % 4][1] for s in range(S)])
+    got = G.f64_of(y)
+    assert G.rel_err(got[:n], ref) < G.BF16_RTOL
+    assert (got[n:] == 7.0).all()          # rows past the last slot are not written
