@@ -40,8 +40,10 @@ static_assert(kFfnLdsBytes >= 2 * (320 + 256) * 128, "two stages of the tallest 
 
 
 // ---- 0. schedule ----------------------------------------------------------------------
-// table[0] = number of tiles; tile i: table[1+3i] = slot, table[2+3i] = first row,
-// table[3+3i] = tile height (320, 256, 192, 128 or 64).
+// The table is one 32-byte header (first word = number of tiles) followed by one 32-byte TileEntry
+// per row tile, which holds everything a workgroup needs to start loading: first row, number
+// of valid rows from there to the end of the slot, tile height (320, 256, 192, 128 or 64) and
+// the slot's two weight pointers.
 //
 // How a slot is cut.  Every tile streams 256 weight rows per k-step whatever its height, so a
 // short tile costs far more than its share of rows (64 rows take about 0.6 of the time of 256) and
@@ -54,6 +56,13 @@ static_assert(kFfnLdsBytes >= 2 * (320 + 256) * 128, "two stages of the tallest 
 // Order of the table.  Slots are taken by descending row count (ties: lower slot first) and a
 // slot's tiles stay together: the workgroups that run side by side then share a slot's weight
 // slices in L2, the long slots start early and the single short tiles fill the tail of the launch.
+struct alignas(16) TileEntry {
+  int32_t row0, rows, height, slot;
+  const void* w13;
+  const void* w2;
+};
+static_assert(sizeof(TileEntry) == 32, "one 32-byte record per tile");
+
 struct SlotCut {
   int n320, n256, n192, tail;  // tail = height of the single 64/128/192-row tile when u <= 3, else 0
   __device__ __forceinline__ int tiles() const { return n320 + n256 + n192 + (tail ? 1 : 0); }
@@ -81,6 +90,8 @@ __device__ __forceinline__ SlotCut cut_slot(int m) {
 }
 
 __global__ __launch_bounds__(256) void ffn_schedule_kernel(const int32_t* __restrict__ slot_offsets,
+                                                           const void* const* __restrict__ w13_ptrs,
+                                                           const void* const* __restrict__ w2_ptrs,
                                                            int S, int max_tiles,
                                                            int32_t* __restrict__ table) {
   __shared__ int32_t rows_of[PROBE_MAX_SLOTS];
@@ -135,6 +146,7 @@ __global__ __launch_bounds__(256) void ffn_schedule_kernel(const int32_t* __rest
   __syncthreads();
   const int total = min(start[S], max_tiles);
   if (tid == 0) table[0] = total;
+  TileEntry* entries = reinterpret_cast<TileEntry*>(table + 8);
   for (int t = tid; t < total; t += 256) {
     int lo = 0, hi = S;  // last position with start[position] <= t
     while (hi - lo > 1) {
@@ -156,9 +168,14 @@ __global__ __launch_bounds__(256) void ffn_schedule_kernel(const int32_t* __rest
     } else {
       height = c.tail;
     }
-    table[1 + 3 * t] = slot;
-    table[2 + 3 * t] = row0;
-    table[3 + 3 * t] = height;
+    TileEntry e;
+    e.row0 = row0;
+    e.rows = slot_offsets[slot + 1] - row0;
+    e.height = height;
+    e.slot = slot;
+    e.w13 = w13_ptrs[slot];
+    e.w2 = w2_ptrs[slot];
+    entries[t] = e;
   }
 }
 
@@ -202,12 +219,12 @@ static int ffn_grid(int max_tiles, int n_cols) {
 // ---- 1. gemm1 + SwiGLU ----------------------------------------------------------------
 template <int MI>
 __device__ __forceinline__ void gemm1_tile(const bf16_t* __restrict__ xp, const bf16_t* __restrict__ w13,
-                                           int row0, int row_end, int n0, int H, int F,
+                                           int row0, int rows, int n0, int H, int F,
                                            bf16_t* __restrict__ hbuf, u32x4* smem) {
+  // rows = valid rows from row0 to the end of the slot (may exceed the tile height)
   const int lane = threadIdx.x & 63;
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wv / 4, wn = wv % 4;
-  const int rows = row_end - row0;  // valid rows from row0 on (may exceed the tile height)
   __amdgpu_buffer_rsrc_t rA = make_rsrc(xp + static_cast<size_t>(row0) * H, static_cast<size_t>(rows) * H * 2);
   __amdgpu_buffer_rsrc_t rB = make_rsrc(w13, static_cast<size_t>(2) * F * H * 2);
   int voff[MI + 4];
@@ -254,40 +271,36 @@ __device__ __forceinline__ void gemm1_tile(const bf16_t* __restrict__ xp, const 
 // one-dimensional launch over (row tile, column block) work items; a column block is 128 gate +
 // 128 up weight rows
 __global__ __launch_bounds__(512, 2) void ffn_gemm1_kernel(const bf16_t* __restrict__ xp,
-                                                           const int32_t* __restrict__ table,
-                                                           const int32_t* __restrict__ slot_offsets,
-                                                           const void* const* __restrict__ w13_ptrs,
-                                                           int H, int F, bf16_t* __restrict__ hbuf) {
+                                                           const int32_t* __restrict__ table, int H, int F,
+                                                           bf16_t* __restrict__ hbuf) {
 #if defined(__HIP_DEVICE_COMPILE__)
   extern __shared__ u32x4 smem[];
   int tile, col;
   if (!ffn_work_item(table[0], (F + 127) / 128, tile, col)) return;
-  const int slot = table[1 + 3 * tile], row0 = table[2 + 3 * tile], height = table[3 + 3 * tile];
-  const int row_end = slot_offsets[slot + 1];
+  const TileEntry e = reinterpret_cast<const TileEntry*>(table + 8)[tile];
   const int n0 = col * 128;
-  const bf16_t* w13 = static_cast<const bf16_t*>(w13_ptrs[slot]);
-  if (height > 256)
-    gemm1_tile<5>(xp, w13, row0, row_end, n0, H, F, hbuf, smem);
-  else if (height > 192)
-    gemm1_tile<4>(xp, w13, row0, row_end, n0, H, F, hbuf, smem);
-  else if (height > 128)
-    gemm1_tile<3>(xp, w13, row0, row_end, n0, H, F, hbuf, smem);
-  else if (height > 64)
-    gemm1_tile<2>(xp, w13, row0, row_end, n0, H, F, hbuf, smem);
+  const bf16_t* w13 = static_cast<const bf16_t*>(e.w13);
+  if (e.height > 256)
+    gemm1_tile<5>(xp, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
+  else if (e.height > 192)
+    gemm1_tile<4>(xp, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
+  else if (e.height > 128)
+    gemm1_tile<3>(xp, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
+  else if (e.height > 64)
+    gemm1_tile<2>(xp, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
   else
-    gemm1_tile<1>(xp, w13, row0, row_end, n0, H, F, hbuf, smem);
+    gemm1_tile<1>(xp, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
 #endif
 }
 
 // ---- 2. gemm2 -------------------------------------------------------------------------
 template <int MI>
 __device__ __forceinline__ void gemm2_tile(const bf16_t* __restrict__ hbuf, const bf16_t* __restrict__ w2,
-                                           int row0, int row_end, int n0, int H, int F,
+                                           int row0, int rows, int n0, int H, int F,
                                            bf16_t* __restrict__ y, u32x4* smem) {
   const int lane = threadIdx.x & 63;
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wv / 4, wn = wv % 4;
-  const int rows = row_end - row0;
   __amdgpu_buffer_rsrc_t rA = make_rsrc(hbuf + static_cast<size_t>(row0) * F, static_cast<size_t>(rows) * F * 2);
   __amdgpu_buffer_rsrc_t rB = make_rsrc(w2, static_cast<size_t>(H) * F * 2);
   int voff[MI + 4];
@@ -322,28 +335,25 @@ __device__ __forceinline__ void gemm2_tile(const bf16_t* __restrict__ hbuf, cons
 
 // one-dimensional launch over (row tile, column block of 256 output columns) work items
 __global__ __launch_bounds__(512, 2) void ffn_gemm2_kernel(const bf16_t* __restrict__ hbuf,
-                                                           const int32_t* __restrict__ table,
-                                                           const int32_t* __restrict__ slot_offsets,
-                                                           const void* const* __restrict__ w2_ptrs,
-                                                           int H, int F, bf16_t* __restrict__ y) {
+                                                           const int32_t* __restrict__ table, int H, int F,
+                                                           bf16_t* __restrict__ y) {
 #if defined(__HIP_DEVICE_COMPILE__)
   extern __shared__ u32x4 smem[];
   int tile, col;
   if (!ffn_work_item(table[0], (H + FBN - 1) / FBN, tile, col)) return;
-  const int slot = table[1 + 3 * tile], row0 = table[2 + 3 * tile], height = table[3 + 3 * tile];
-  const int row_end = slot_offsets[slot + 1];
+  const TileEntry e = reinterpret_cast<const TileEntry*>(table + 8)[tile];
   const int n0 = col * FBN;
-  const bf16_t* w2 = static_cast<const bf16_t*>(w2_ptrs[slot]);
-  if (height > 256)
-    gemm2_tile<5>(hbuf, w2, row0, row_end, n0, H, F, y, smem);
-  else if (height > 192)
-    gemm2_tile<4>(hbuf, w2, row0, row_end, n0, H, F, y, smem);
-  else if (height > 128)
-    gemm2_tile<3>(hbuf, w2, row0, row_end, n0, H, F, y, smem);
-  else if (height > 64)
-    gemm2_tile<2>(hbuf, w2, row0, row_end, n0, H, F, y, smem);
+  const bf16_t* w2 = static_cast<const bf16_t*>(e.w2);
+  if (e.height > 256)
+    gemm2_tile<5>(hbuf, w2, e.row0, e.rows, n0, H, F, y, smem);
+  else if (e.height > 192)
+    gemm2_tile<4>(hbuf, w2, e.row0, e.rows, n0, H, F, y, smem);
+  else if (e.height > 128)
+    gemm2_tile<3>(hbuf, w2, e.row0, e.rows, n0, H, F, y, smem);
+  else if (e.height > 64)
+    gemm2_tile<2>(hbuf, w2, e.row0, e.rows, n0, H, F, y, smem);
   else
-    gemm2_tile<1>(hbuf, w2, row0, row_end, n0, H, F, y, smem);
+    gemm2_tile<1>(hbuf, w2, e.row0, e.rows, n0, H, F, y, smem);
 #endif
 }
 
@@ -356,7 +366,7 @@ static FfnShape ffn_shape(int S, int F, int max_rows) {
   FfnShape s;
   s.max_tiles = max_rows / 256 + S;
   s.h_bytes = align_up(static_cast<size_t>(max_rows > 0 ? max_rows : 1) * F * sizeof(bf16_t), 256);
-  s.table_bytes = align_up((1 + 3 * static_cast<size_t>(s.max_tiles)) * sizeof(int32_t), 256);
+  s.table_bytes = align_up((1 + static_cast<size_t>(s.max_tiles)) * sizeof(TileEntry), 256);
   return s;
 }
 
@@ -422,10 +432,11 @@ extern "C" int probe_grouped_ffn(const void* xp_bf16, const int32_t* slot_offset
   hipStream_t st = static_cast<hipStream_t>(stream);
   bf16_t* hbuf = static_cast<bf16_t*>(workspace);
   int32_t* table = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + sh.h_bytes);
-  hipLaunchKernelGGL(ffn_schedule_kernel, dim3(1), dim3(256), 0, st, slot_offsets, S, sh.max_tiles, table);
+  hipLaunchKernelGGL(ffn_schedule_kernel, dim3(1), dim3(256), 0, st, slot_offsets, w13_ptrs, w2_ptrs, S, sh.max_tiles,
+                     table);
   hipLaunchKernelGGL(ffn_gemm1_kernel, dim3(ffn_grid(sh.max_tiles, (F + 127) / 128)), dim3(512), kFfnLdsBytes, st,
-                     static_cast<const bf16_t*>(xp_bf16), table, slot_offsets, w13_ptrs, H, F, hbuf);
+                     static_cast<const bf16_t*>(xp_bf16), table, H, F, hbuf);
   hipLaunchKernelGGL(ffn_gemm2_kernel, dim3(ffn_grid(sh.max_tiles, (H + FBN - 1) / FBN)), dim3(512), kFfnLdsBytes, st,
-                     hbuf, table, slot_offsets, w2_ptrs, H, F, static_cast<bf16_t*>(y_bf16));
+                     hbuf, table, H, F, static_cast<bf16_t*>(y_bf16));
   return check_launch("probe_grouped_ffn");
 }
