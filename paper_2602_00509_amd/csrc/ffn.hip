@@ -239,29 +239,32 @@ __device__ __forceinline__ void gemm1_tile(const bf16_t* __restrict__ xp, const 
                  voff + MI);
   f32x16 acc[MI][2];
   zero_acc<MI>(acc);
-  gemm_mainloop<MI, 2, 1, (MI >= 3 ? 2 : 3)>(rA, rB, voff, 0, H, smem, wv, lane, acc);
+  gemm_mainloop<MI, 2, 1, (MI >= 3 ? 2 : 3), true>(rA, rB, voff, 0, H, smem, wv, lane, acc);
 
-  // The weight fragment is the MFMA's row operand, so accumulator registers 4q..4q+3 of a lane
-  // are four consecutive output columns of one output row: one 8-byte store each.
+  // Accumulator registers 8g .. 8g+7 of a lane are eight consecutive output columns of one output
+  // row (see gemm_mainloop, PERM): one 16-byte store each.
   const int row_in = 32 * MI * wm + (lane & 31);
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi) {
     const int row = row_in + 32 * mi;
     if (row < rows) {
-      bf16_t* dst = hbuf + static_cast<size_t>(row0 + row) * F + n0 + 32 * wn + 4 * (lane >> 5);
+      const int cbase = n0 + 32 * wn + 8 * (lane >> 5);
+      bf16_t* dst = hbuf + static_cast<size_t>(row0 + row) * F + cbase;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        if (n0 + 32 * wn + 8 * q < F) {  // F % 8 == 0: an 8-column group is in or out as a whole
-          float hv[4];
+      for (int g = 0; g < 2; ++g) {
+        if (cbase + 16 * g < F) {  // F % 8 == 0: an 8-column group is in or out as a whole
+          float hv[8];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            float g = acc[mi][0][4 * q + e], u = acc[mi][1][4 * q + e];
-            hv[e] = g / (1.f + __expf(-g)) * u;
+          for (int e = 0; e < 8; ++e) {
+            float gt = acc[mi][0][8 * g + e], up = acc[mi][1][8 * g + e];
+            hv[e] = gt / (1.f + __expf(-gt)) * up;
           }
-          uint2 pk;
+          uint4 pk;
           pk.x = pack_bf16x2(hv[0], hv[1]);
           pk.y = pack_bf16x2(hv[2], hv[3]);
-          *reinterpret_cast<uint2*>(dst + 8 * q) = pk;
+          pk.z = pack_bf16x2(hv[4], hv[5]);
+          pk.w = pack_bf16x2(hv[6], hv[7]);
+          *reinterpret_cast<uint4*>(dst + 16 * g) = pk;
         }
       }
     }
@@ -308,7 +311,7 @@ __device__ __forceinline__ void gemm2_tile(const bf16_t* __restrict__ hbuf, cons
   dma_offsets<4>(wv, lane, F * 2, [&](int j) { return min(n0 + j, H - 1); }, voff + MI);
   f32x16 acc[MI][2];
   zero_acc<MI>(acc);
-  gemm_mainloop<MI, 2, 1, (MI >= 3 ? 2 : 3)>(rA, rB, voff, 0, F, smem, wv, lane, acc);
+  gemm_mainloop<MI, 2, 1, (MI >= 3 ? 2 : 3), true>(rA, rB, voff, 0, F, smem, wv, lane, acc);
 
   const int row_in = 32 * MI * wm + (lane & 31);
 #pragma unroll
@@ -317,15 +320,17 @@ __device__ __forceinline__ void gemm2_tile(const bf16_t* __restrict__ hbuf, cons
     if (row < rows) {
 #pragma unroll
       for (int ni = 0; ni < 2; ++ni) {
-        const int cbase = n0 + 64 * wn + 32 * ni;
-        bf16_t* dst = y + static_cast<size_t>(row0 + row) * H + cbase + 4 * (lane >> 5);
+        const int cbase = n0 + 64 * wn + 32 * ni + 8 * (lane >> 5);
+        bf16_t* dst = y + static_cast<size_t>(row0 + row) * H + cbase;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          if (cbase + 8 * q < H) {
-            uint2 pk;
-            pk.x = pack_bf16x2(acc[mi][ni][4 * q], acc[mi][ni][4 * q + 1]);
-            pk.y = pack_bf16x2(acc[mi][ni][4 * q + 2], acc[mi][ni][4 * q + 3]);
-            *reinterpret_cast<uint2*>(dst + 8 * q) = pk;
+        for (int g = 0; g < 2; ++g) {
+          if (cbase + 16 * g < H) {
+            uint4 pk;
+            pk.x = pack_bf16x2(acc[mi][ni][8 * g + 0], acc[mi][ni][8 * g + 1]);
+            pk.y = pack_bf16x2(acc[mi][ni][8 * g + 2], acc[mi][ni][8 * g + 3]);
+            pk.z = pack_bf16x2(acc[mi][ni][8 * g + 4], acc[mi][ni][8 * g + 5]);
+            pk.w = pack_bf16x2(acc[mi][ni][8 * g + 6], acc[mi][ni][8 * g + 7]);
+            *reinterpret_cast<uint4*>(dst + 16 * g) = pk;
           }
         }
       }

@@ -25,7 +25,15 @@ __device__ __forceinline__ void wait_vm_lgkm0() {  // s_waitcnt vmcnt(N) lgkmcnt
 // this lane's byte offset for DMA instruction j (MI instructions for A, then BW for B); k0 is
 // the first k of this call's K range and K its length (a multiple of 64).
 // NST = LDS stages (2 or 3); a DMA batch is issued NST k-steps ahead of its use.
-template <int MI, int NI, int PL, int NST>
+//
+// Accumulator layout.  The B fragment is the MFMA's row operand, so with PERM = false registers
+// 4q .. 4q+3 of lane l hold output row (l % 32) of the A block and the four consecutive output
+// columns 8q + 4(l / 32) .. +3 of the B block.  With PERM = true, MFMA row position i is fed B row
+// i with bits 2 and 3 exchanged; registers 8g .. 8g+7 then hold the EIGHT consecutive columns
+// 16g + 8(l / 32) .. +7, a 16-byte bf16 store per lane and 32 contiguous bytes per row and store
+// instruction.  Sixteen consecutive positions still read sixteen consecutive LDS rows, so the
+// fragment reads stay free of bank conflicts.
+template <int MI, int NI, int PL, int NST, bool PERM = false>
 __device__ __forceinline__ void gemm_mainloop(__amdgpu_buffer_rsrc_t rA, __amdgpu_buffer_rsrc_t rB,
                                               const int (&voff)[MI + NI * PL * 2], int k0, int K,
                                               u32x4* smem, int wv, int lane, f32x16 (&acc)[MI][NI]) {
@@ -49,21 +57,23 @@ __device__ __forceinline__ void gemm_mainloop(__amdgpu_buffer_rsrc_t rA, __amdgp
     for (int j = 0; j < LPW; ++j) issue_one(st, j, (k0 + kt * FBK) * 2);
   };
   int offA[MI], offB[NB];
+  const int brow = PERM ? ((lane & 19) | ((lane & 4) << 1) | ((lane & 8) >> 1)) : (lane & 31);
 #pragma unroll
   for (int i = 0; i < MI; ++i) offA[i] = (32 * MI * wm + 32 * i + (lane & 31)) * 8;
 #pragma unroll
   for (int j = 0; j < NI; ++j)
 #pragma unroll
     for (int p = 0; p < PL; ++p)
-      offB[j * PL + p] = BM * 8 + (p * 128 * NI + 32 * NI * wn + 32 * j + (lane & 31)) * 8;
+      offB[j * PL + p] = BM * 8 + (p * 128 * NI + 32 * NI * wn + 32 * j + brow) * 8;
   const int swz = ((lane & 31) >> 1) & 7;  // (row >> 1) & 7: every 32-row block starts at a multiple of 32
+  const int swzB = (brow >> 1) & 7;
   auto read_frags = [&](int st, int kk, u32x4(&a)[MI], u32x4(&b)[NB]) {
     const u32x4* sbase = smem + st * kStage;
-    const int pc = (2 * kk + (lane >> 5)) ^ swz;
+    const int pc = (2 * kk + (lane >> 5)) ^ swz, pcB = (2 * kk + (lane >> 5)) ^ swzB;
 #pragma unroll
     for (int i = 0; i < MI; ++i) a[i] = sbase[offA[i] + pc];
 #pragma unroll
-    for (int j = 0; j < NB; ++j) b[j] = sbase[offB[j] + pc];
+    for (int j = 0; j < NB; ++j) b[j] = sbase[offB[j] + pcB];
   };
   // the weight fragment is the row operand: a lane's accumulator registers 4q..4q+3 are four
   // consecutive output columns of one output row
