@@ -63,6 +63,8 @@ struct alignas(16) TileEntry {
 };
 static_assert(sizeof(TileEntry) == 32, "one 32-byte record per tile");
 
+constexpr bool kInterleave = true;
+
 struct SlotCut {
   int n320, n256, n192, tail;  // tail = height of the single 64/128/192-row tile when u <= 3, else 0
   __device__ __forceinline__ int tiles() const { return n320 + n256 + n192 + (tail ? 1 : 0); }
@@ -95,6 +97,9 @@ __global__ __launch_bounds__(256) void ffn_schedule_kernel(const int32_t* __rest
                                                            int S, int max_tiles,
                                                            int32_t* __restrict__ table) {
   __shared__ int32_t rows_of[PROBE_MAX_SLOTS];
+  __shared__ int32_t first_of[PROBE_MAX_SLOTS];
+  __shared__ const void* w13_of[PROBE_MAX_SLOTS];
+  __shared__ const void* w2_of[PROBE_MAX_SLOTS];
   __shared__ int32_t slot_at[PROBE_MAX_SLOTS];       // slot at each position of the sorted order
   __shared__ int32_t start[PROBE_MAX_SLOTS + 1];     // first tile of each position (exclusive prefix)
   __shared__ int32_t wave_tot[4];
@@ -103,8 +108,15 @@ __global__ __launch_bounds__(256) void ffn_schedule_kernel(const int32_t* __rest
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int s = tid * 4 + i;
-    m[i] = (s < S) ? max(slot_offsets[s + 1] - slot_offsets[s], 0) : 0;
-    if (s < S) rows_of[s] = m[i];
+    m[i] = 0;
+    if (s < S) {
+      const int first = slot_offsets[s];
+      m[i] = max(slot_offsets[s + 1] - first, 0);
+      rows_of[s] = m[i];
+      first_of[s] = first;
+      w13_of[s] = w13_ptrs[s];
+      w2_of[s] = w2_ptrs[s];
+    }
   }
   __syncthreads();
   // position of a slot = number of slots that come before it
@@ -147,13 +159,25 @@ __global__ __launch_bounds__(256) void ffn_schedule_kernel(const int32_t* __rest
   const int total = min(start[S], max_tiles);
   if (tid == 0) table[0] = total;
   TileEntry* entries = reinterpret_cast<TileEntry*>(table + 8);
-  for (int t = tid; t < total; t += 256) {
+  // positions [0, big) hold the slots of more than 192 rows: tiles [0, nb) are theirs, the ns single
+  // short tiles follow
+  int big = 0;
+  for (int hi = S; big < hi;) {
+    const int mid = (big + hi) >> 1;
+    if (rows_of[slot_at[mid]] > 192) big = mid + 1; else hi = mid;
+  }
+  const int nb = min(start[big], total), ns = total - nb;
+  for (int p = tid; p < total; p += 256) {
+    // entry p of the table: the short tiles are spread evenly over the table
+    const int before = static_cast<int>(static_cast<long>(p) * ns / total);
+    const bool is_short = static_cast<int>(static_cast<long>(p + 1) * ns / total) > before;
+    const int t = kInterleave ? (is_short ? nb + before : p - before) : p;
     int lo = 0, hi = S;  // last position with start[position] <= t
     while (hi - lo > 1) {
       int mid = (lo + hi) >> 1;
       if (start[mid] <= t) lo = mid; else hi = mid;
     }
-    const int slot = slot_at[lo], first = slot_offsets[slot];
+    const int slot = slot_at[lo], first = first_of[slot];
     const SlotCut c = cut_slot(rows_of[slot]);
     int i = t - start[lo], row0 = first, height;
     if (i < c.n320) {
@@ -170,12 +194,12 @@ __global__ __launch_bounds__(256) void ffn_schedule_kernel(const int32_t* __rest
     }
     TileEntry e;
     e.row0 = row0;
-    e.rows = slot_offsets[slot + 1] - row0;
+    e.rows = first + rows_of[slot] - row0;
     e.height = height;
     e.slot = slot;
-    e.w13 = w13_ptrs[slot];
-    e.w2 = w2_ptrs[slot];
-    entries[t] = e;
+    e.w13 = w13_of[slot];
+    e.w2 = w2_of[slot];
+    entries[p] = e;
   }
 }
 
