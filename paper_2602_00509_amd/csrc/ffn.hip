@@ -46,12 +46,12 @@ static_assert(kFfnLdsBytes >= 2 * (320 + 256) * 128, "two stages of the tallest 
 // the slot's two weight pointers.
 //
 // How a slot is cut.  Every tile streams 256 weight rows per k-step whatever its height, so a
-// short tile costs far more than its share of rows (64 rows take about 0.6 of the time of 256) and
-// the 320-row tile is the cheapest per row.  A slot of M rows, u = ceil(M / 64), becomes a tiles of
-// 320 and b tiles of 256 with 5a + 4b = u and a as large as possible: b = 4u mod 5, which exists
-// whenever 4b <= u (every u >= 12).  The six values of u without such a cut get one short tile:
-//   u = 1, 2, 3: one tile of 64u rows;  6: 192 + 192;  7: 256 + 192;  11: 256 + 256 + 192.
-// Inside a slot the 320s come first, then the 256s, then the 192s.
+// short tile costs far more than its share of rows (64 rows take almost half the time of 256).
+// A slot of M rows, u = ceil(M / 64), becomes a tiles of 320 and b tiles of 256 with 5a + 4b = u
+// and a as large as possible: b = 4u mod 5, which exists whenever 4b <= u (every u >= 12).  The
+// six values of u without such a cut end in one short tile, chosen by measured tile cost:
+//   u = 1, 2, 3: one tile of 64u rows;  6: 256 + 128;  7: 320 + 128;  11: 320 + 256 + 128.
+// Inside a slot the 320s come first, then the 256s, then the short tile.
 //
 // Order of the table.  Slots are taken by descending row count (ties: lower slot first) and a
 // slot's tiles stay together: the workgroups that run side by side then share a slot's weight
@@ -66,12 +66,12 @@ static_assert(sizeof(TileEntry) == 32, "one 32-byte record per tile");
 constexpr bool kInterleave = true;
 
 struct SlotCut {
-  int n320, n256, n192, tail;  // tail = height of the single 64/128/192-row tile when u <= 3, else 0
-  __device__ __forceinline__ int tiles() const { return n320 + n256 + n192 + (tail ? 1 : 0); }
+  int n320, n256, tail;  // tail = height of the one short tile (64, 128 or 192), 0 if there is none
+  __device__ __forceinline__ int tiles() const { return n320 + n256 + (tail ? 1 : 0); }
 };
 
 __device__ __forceinline__ SlotCut cut_slot(int m) {
-  SlotCut c = {0, 0, 0, 0};
+  SlotCut c = {0, 0, 0};
   const int u = (m + 63) >> 6;
   if (u == 0) return c;
   if (u <= 3) {
@@ -82,11 +82,10 @@ __device__ __forceinline__ SlotCut cut_slot(int m) {
   if (4 * b <= u) {
     c.n256 = b;
     c.n320 = (u - 4 * b) / 5;
-  } else if (u == 6) {
-    c.n192 = 2;
-  } else {  // u == 7 or u == 11
-    c.n256 = u == 7 ? 1 : 2;
-    c.n192 = 1;
+  } else {  // u == 6, 7 or 11
+    c.n320 = u == 6 ? 0 : 1;
+    c.n256 = u == 7 ? 0 : 1;
+    c.tail = 128;
   }
   return c;
 }
@@ -186,10 +185,8 @@ __global__ __launch_bounds__(256) void ffn_schedule_kernel(const int32_t* __rest
     } else if ((i -= c.n320) < c.n256) {
       row0 += c.n320 * 320 + i * 256;
       height = 256;
-    } else if ((i -= c.n256) < c.n192) {
-      row0 += c.n320 * 320 + c.n256 * 256 + i * 192;
-      height = 192;
     } else {
+      row0 += c.n320 * 320 + c.n256 * 256;
       height = c.tail;
     }
     TileEntry e;
