@@ -143,8 +143,11 @@ __global__ __launch_bounds__(256, 2) void gate_gemm_kernel(const bf16_t* __restr
 // stages of 64 KB = 128 token rows + 3 planes x 128 expert rows, three MFMAs (one per plane) per
 // operand pair into one accumulator.  The weight fragment is the MFMA's row operand, so a lane
 // ends with four consecutive experts of one token per register quad: 16-byte stores.
-constexpr int kGateLdsBytes = 2 * (128 + 384) * 128;
+// MI = 2: 128 tokens per workgroup; MI = 4: 256 tokens (two stages of 80 KB, all of the LDS), which
+// moves a third less operand data per MFMA and is used for large batches.
+constexpr int kGateLdsBytes = 2 * (256 + 384) * 128;
 
+template <int MI>
 __global__ __launch_bounds__(512, 2) void gate_gemm_dma_kernel(const bf16_t* __restrict__ x,
                                                                const bf16_t* __restrict__ planes,
                                                                int T, int H, int E, int k_chunk,
@@ -154,27 +157,27 @@ __global__ __launch_bounds__(512, 2) void gate_gemm_dma_kernel(const bf16_t* __r
   const int lane = threadIdx.x & 63;
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wv / 4, wn = wv % 4;
-  const int m0 = blockIdx.x * GBM, n0 = blockIdx.y * GBN, ks = blockIdx.z;
+  const int m0 = blockIdx.x * (64 * MI), n0 = blockIdx.y * GBN, ks = blockIdx.z;
   const int kbeg = ks * k_chunk, klen = min(H, kbeg + k_chunk) - kbeg;
   if (klen <= 0) return;
   const int rows = T - m0;
   __amdgpu_buffer_rsrc_t rA = make_rsrc(x + static_cast<size_t>(m0) * H, static_cast<size_t>(rows) * H * 2);
   __amdgpu_buffer_rsrc_t rB = make_rsrc(planes, static_cast<size_t>(3) * E * H * 2);
-  int voff[2 + 6];
-  dma_offsets<2>(wv, lane, H * 2, [&](int r) { return min(r, rows - 1); }, voff);
+  int voff[MI + 6];
+  dma_offsets<MI>(wv, lane, H * 2, [&](int r) { return min(r, rows - 1); }, voff);
   // B-tile row j: plane j / 128, expert n0 + j % 128 (clamped; columns past E are masked at the store)
-  dma_offsets<6>(wv, lane, H * 2, [&](int j) { return (j >> 7) * E + min(n0 + (j & 127), E - 1); }, voff + 2);
-  f32x16 acc[2][1];
+  dma_offsets<6>(wv, lane, H * 2, [&](int j) { return (j >> 7) * E + min(n0 + (j & 127), E - 1); }, voff + MI);
+  f32x16 acc[MI][1];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[i][0][r] = 0.f;
-  gemm_mainloop<2, 1, 3, 2>(rA, rB, voff, kbeg, klen, smem, wv, lane, acc);
+  gemm_mainloop<MI, 1, 3, 2>(rA, rB, voff, kbeg, klen, smem, wv, lane, acc);
 
   const bool vec = (E & 3) == 0;
 #pragma unroll
-  for (int mi = 0; mi < 2; ++mi) {
-    const int row = 64 * wm + 32 * mi + (lane & 31);
+  for (int mi = 0; mi < MI; ++mi) {
+    const int row = 32 * MI * wm + 32 * mi + (lane & 31);
     if (row < rows) {
       float* dst = partial + (static_cast<long>(ks) * T + m0 + row) * E;
 #pragma unroll
@@ -205,8 +208,11 @@ static int gate_prepare() {
   }
   std::lock_guard<std::mutex> lock(mu);
   if (done[dev]) return PROBE_OK;
-  hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(gate_gemm_dma_kernel),
+  hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(gate_gemm_dma_kernel<2>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kGateLdsBytes);
+  if (err == hipSuccess)
+    err = hipFuncSetAttribute(reinterpret_cast<const void*>(gate_gemm_dma_kernel<4>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, kGateLdsBytes);
   if (err != hipSuccess) {
     set_error("probe_route_topk: cannot reserve %d bytes of LDS: %s", kGateLdsBytes, hipGetErrorString(err));
     return PROBE_EHIP;
@@ -448,17 +454,23 @@ __global__ __launch_bounds__(256) void gate_softmax_topk_kernel(
 }
 
 struct RouteShape {
+  int bm;  // tokens per workgroup of the gemm (128 or 256)
   int mt, nt, ks, k_chunk;
   size_t planes_bytes, partial_bytes;
 };
 
 static RouteShape route_shape(int T, int H, int E) {
   RouteShape s;
-  s.mt = (T + GBM - 1) / GBM;
+  // 256-token tiles when a split of 8 or less still gives every CU a workgroup; they aim at one
+  // workgroup per CU (fewer, longer K ranges and half the partial sums), 128-token tiles at two
+  const bool dma = H % 64 == 0 && static_cast<size_t>(3) * E * H * 2 <= 0x7fffffffull;
   s.nt = (E + GBN - 1) / GBN;
+  s.bm = (dma && static_cast<long>((T + 255) / 256) * s.nt * 8 >= 256) ? 256 : GBM;
+  s.mt = (T + s.bm - 1) / s.bm;
   int tiles = s.mt * s.nt;
   int ksteps = (H + GBK - 1) / GBK;
-  int want = tiles > 0 ? (512 + tiles - 1) / tiles : 1;
+  const int target = s.bm == 256 ? 256 : 512;
+  int want = tiles > 0 ? (target + tiles - 1) / tiles : 1;
   if (want < 1) want = 1;
   if (want > ksteps) want = ksteps;
   int steps_per = (ksteps + want - 1) / want;
@@ -502,8 +514,12 @@ static int route_impl(const char* name, const void* x_bf16, const float* w_gate,
                      0, st, w_gate, n, planes, expert_counts, E);
   if (T > 0) {
     if (H % 64 == 0 && static_cast<size_t>(3) * E * H * 2 <= 0x7fffffffull) {
-      hipLaunchKernelGGL(gate_gemm_dma_kernel, dim3(sh.mt, sh.nt, sh.ks), dim3(512), kGateLdsBytes, st,
-                         static_cast<const bf16_t*>(x_bf16), planes, T, H, E, sh.k_chunk, partial);
+      if (sh.bm == 256)
+        hipLaunchKernelGGL(gate_gemm_dma_kernel<4>, dim3(sh.mt, sh.nt, sh.ks), dim3(512), kGateLdsBytes, st,
+                           static_cast<const bf16_t*>(x_bf16), planes, T, H, E, sh.k_chunk, partial);
+      else
+        hipLaunchKernelGGL(gate_gemm_dma_kernel<2>, dim3(sh.mt, sh.nt, sh.ks), dim3(512), kGateLdsBytes, st,
+                           static_cast<const bf16_t*>(x_bf16), planes, T, H, E, sh.k_chunk, partial);
     } else {
       hipLaunchKernelGGL(gate_gemm_kernel, dim3(sh.mt, sh.nt, sh.ks), dim3(256), 0, st,
                          static_cast<const bf16_t*>(x_bf16), planes, T, H, E, sh.k_chunk, partial);

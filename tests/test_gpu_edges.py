@@ -114,6 +114,25 @@ def test_route_when_hidden_size_is_not_a_multiple_of_64(oracle, probe, G, T, H, 
     np.testing.assert_array_equal(g["counts"].cpu().numpy(), np.bincount(g["idx"].cpu().numpy().ravel(), minlength=E))
 
 
+@pytest.mark.parametrize("T,H,E,k", [(8200, 256, 256, 8), (4100, 1024, 200, 6), (2049, 128, 130, 4)])
+def test_route_on_256_token_tiles_with_a_ragged_last_tile(oracle, probe, G, T, H, E, k):
+    """Large batches take the 256-token tile of the gate GEMM; T is not a multiple of the tile, E not
+    always one of 128, and the K range of one split is as short as one step."""
+    print("case route T=%d H=%d E=%d" % (T, H, E), flush=True)
+    rng = np.random.default_rng(T)
+    x = wl.f32_to_bf16_bits(rng.standard_normal((T, H), dtype=np.float32))
+    wg = (rng.standard_normal((E, H), dtype=np.float32) * np.float32(0.05))
+    b = rng.standard_normal((3, E)).astype(np.float32)
+    tpg = 1500
+    g = probe.route_topk(G.dev_bf16(x), torch.from_numpy(wg).cuda(), torch.from_numpy(b).cuda(), tpg, k, True,
+                         want_probs=True)
+    torch.cuda.synchronize()
+    o = oracle.route_topk(x, wg, b, tpg, k, True)
+    G.check_route(g, o, k, True)
+    np.testing.assert_allclose(g["probs"].cpu().numpy(), o["probs"], rtol=0, atol=G.PROB_ATOL)
+    np.testing.assert_array_equal(g["counts"].cpu().numpy(), np.bincount(g["idx"].cpu().numpy().ravel(), minlength=E))
+
+
 def test_determinism_and_plan_invariance(oracle, probe, G):
     """Two runs are bit-identical; with every replica local, any plan gives the same layer output."""
     print("case determinism / plan invariance", flush=True)
