@@ -29,7 +29,7 @@ PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E
 # L2-miss fetch + write bytes of ffn_gemm1 + ffn_gemm2 per call, from two rocprofv3 --pmc runs
 # (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0 after calibration on a plain 1 GiB copy kernel); the figures and
 # the commands are in profiles/bench_cfg3_hbm_traffic.md.  Only known for configuration 3.
-MEASURED_FFN_TRAFFIC_BYTES = {3: 6.33e9}
+MEASURED_FFN_TRAFFIC_BYTES = {3: 7.17e9}
 
 
 def log(*a):
