@@ -165,7 +165,8 @@ int probe_permute(const int32_t* topk_idx, const probe_plan* plan, const void* x
  *
  * bf16 inputs, fp32 accumulation on the matrix cores, h rounded to bf16 between the two
  * GEMMs, bf16 output.  An empty slot does no work and its weights are not read.
- * Limits: H % 64 == 0, F % 64 == 0, 1 <= S <= 1024, one expert's w13 below 2 GiB.
+ * Limits: H % 64 == 0, F % 64 == 0, H and F at most 2^21, 1 <= S <= 1024, one expert's w13 below
+ * 2 GiB.
  */
 size_t probe_grouped_ffn_workspace_bytes(int S, int H, int F, int max_rows);
 

@@ -263,30 +263,31 @@ __device__ __forceinline__ void gemm1_tile(const bf16_t* __restrict__ xp, const 
   gemm_mainloop<MI, 2, 1, (MI >= 3 ? 2 : 3), true>(rA, rB, voff, 0, H, smem, wv, lane, acc);
 
   // Accumulator registers 8g .. 8g+7 of a lane are eight consecutive output columns of one output
-  // row (see gemm_mainloop, PERM): one 16-byte store each.
+  // row (see gemm_mainloop, PERM): one 16-byte store each.  The stores go through a buffer
+  // descriptor that ends with the tile's last valid row, so rows past it are dropped by the
+  // bounds check instead of a branch.
+  const int valid = min(rows, 64 * MI);
+  __amdgpu_buffer_rsrc_t rH = make_rsrc(hbuf + static_cast<size_t>(row0) * F, static_cast<size_t>(valid) * F * 2);
   const int row_in = 32 * MI * wm + (lane & 31);
+  const int cbase = n0 + 32 * wn + 8 * (lane >> 5);
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi) {
-    const int row = row_in + 32 * mi;
-    if (row < rows) {
-      const int cbase = n0 + 32 * wn + 8 * (lane >> 5);
-      bf16_t* dst = hbuf + static_cast<size_t>(row0 + row) * F + cbase;
+    const int off = ((row_in + 32 * mi) * F + cbase) * 2;
 #pragma unroll
-      for (int g = 0; g < 2; ++g) {
-        if (cbase + 16 * g < F) {  // F % 8 == 0: an 8-column group is in or out as a whole
-          float hv[8];
+    for (int g = 0; g < 2; ++g) {
+      if (cbase + 16 * g < F) {  // F % 8 == 0: an 8-column group is in or out as a whole
+        float hv[8];
 #pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            float gt = acc[mi][0][8 * g + e], up = acc[mi][1][8 * g + e];
-            hv[e] = gt / (1.f + __expf(-gt)) * up;
-          }
-          uint4 pk;
-          pk.x = pack_bf16x2(hv[0], hv[1]);
-          pk.y = pack_bf16x2(hv[2], hv[3]);
-          pk.z = pack_bf16x2(hv[4], hv[5]);
-          pk.w = pack_bf16x2(hv[6], hv[7]);
-          *reinterpret_cast<uint4*>(dst + 16 * g) = pk;
+        for (int e = 0; e < 8; ++e) {
+          float gt = acc[mi][0][8 * g + e], up = acc[mi][1][8 * g + e];
+          hv[e] = gt / (1.f + __expf(-gt)) * up;
         }
+        u32x4 pk;
+        pk[0] = pack_bf16x2(hv[0], hv[1]);
+        pk[1] = pack_bf16x2(hv[2], hv[3]);
+        pk[2] = pack_bf16x2(hv[4], hv[5]);
+        pk[3] = pack_bf16x2(hv[6], hv[7]);
+        __builtin_amdgcn_raw_buffer_store_b128(pk, rH, off + 32 * g, 0, 0);
       }
     }
   }
@@ -334,25 +335,24 @@ __device__ __forceinline__ void gemm2_tile(const bf16_t* __restrict__ hbuf, cons
   zero_acc<MI>(acc);
   gemm_mainloop<MI, 2, 1, (MI >= 3 ? 2 : 3), true>(rA, rB, voff, 0, F, smem, wv, lane, acc);
 
+  const int valid = min(rows, 64 * MI);  // rows past it are dropped by the descriptor's bounds check
+  __amdgpu_buffer_rsrc_t rY = make_rsrc(y + static_cast<size_t>(row0) * H, static_cast<size_t>(valid) * H * 2);
   const int row_in = 32 * MI * wm + (lane & 31);
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi) {
-    const int row = row_in + 32 * mi;
-    if (row < rows) {
 #pragma unroll
-      for (int ni = 0; ni < 2; ++ni) {
-        const int cbase = n0 + 64 * wn + 32 * ni + 8 * (lane >> 5);
-        bf16_t* dst = y + static_cast<size_t>(row0 + row) * H + cbase;
+    for (int ni = 0; ni < 2; ++ni) {
+      const int cbase = n0 + 64 * wn + 32 * ni + 8 * (lane >> 5);
+      const int off = ((row_in + 32 * mi) * H + cbase) * 2;
 #pragma unroll
-        for (int g = 0; g < 2; ++g) {
-          if (cbase + 16 * g < H) {
-            uint4 pk;
-            pk.x = pack_bf16x2(acc[mi][ni][8 * g + 0], acc[mi][ni][8 * g + 1]);
-            pk.y = pack_bf16x2(acc[mi][ni][8 * g + 2], acc[mi][ni][8 * g + 3]);
-            pk.z = pack_bf16x2(acc[mi][ni][8 * g + 4], acc[mi][ni][8 * g + 5]);
-            pk.w = pack_bf16x2(acc[mi][ni][8 * g + 6], acc[mi][ni][8 * g + 7]);
-            *reinterpret_cast<uint4*>(dst + 16 * g) = pk;
-          }
+      for (int g = 0; g < 2; ++g) {
+        if (cbase + 16 * g < H) {
+          u32x4 pk;
+          pk[0] = pack_bf16x2(acc[mi][ni][8 * g + 0], acc[mi][ni][8 * g + 1]);
+          pk[1] = pack_bf16x2(acc[mi][ni][8 * g + 2], acc[mi][ni][8 * g + 3]);
+          pk[2] = pack_bf16x2(acc[mi][ni][8 * g + 4], acc[mi][ni][8 * g + 5]);
+          pk[3] = pack_bf16x2(acc[mi][ni][8 * g + 6], acc[mi][ni][8 * g + 7]);
+          __builtin_amdgcn_raw_buffer_store_b128(pk, rY, off + 32 * g, 0, 0);
         }
       }
     }
@@ -441,6 +441,8 @@ extern "C" int probe_grouped_ffn(const void* xp_bf16, const int32_t* slot_offset
                 PROBE_MAX_SLOTS, S, H, F);
   PROBE_REQUIRE(static_cast<size_t>(2) * F * H * 2 <= 0x7fffffffull, PROBE_EUNSUPPORTED,
                 "probe_grouped_ffn: one expert's w13 must stay below 2 GiB (H=%d F=%d)", H, F);
+  PROBE_REQUIRE(H <= (1 << 21) && F <= (1 << 21), PROBE_EUNSUPPORTED,
+                "probe_grouped_ffn: H and F must not exceed 2^21 (32-bit byte offsets inside a row tile)");
   if (max_rows == 0) return PROBE_OK;
   PROBE_REQUIRE(xp_bf16 && slot_offsets && w13_ptrs && w2_ptrs && y_bf16, PROBE_EINVAL,
                 "probe_grouped_ffn: null pointer");

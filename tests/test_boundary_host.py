@@ -78,6 +78,8 @@ def test_bad_arguments_are_rejected_without_a_launch(L):
     # grouped ffn
     assert L.probe_grouped_ffn(fake, fake, fake, fake, 4, 100, 128, 64, fake, fake, big, None) == -2      # H % 64
     assert L.probe_grouped_ffn(fake, fake, fake, fake, 4, 128, 96, 64, fake, fake, big, None) == -2       # F % 64
+    assert L.probe_grouped_ffn(fake, fake, fake, fake, 4, (1 << 21) + 64, 64, 64, fake, fake, big, None) == -2  # H > 2^21
+    assert b"2^21" in L.probe_last_error_string()
     assert L.probe_grouped_ffn(fake, fake, fake, fake, 0, 128, 128, 64, fake, fake, big, None) == -1
     assert L.probe_grouped_ffn(None, fake, fake, fake, 4, 128, 128, 64, fake, fake, big, None) == -1
     assert L.probe_grouped_ffn(fake, fake, fake, fake, 4, 128, 128, 64, fake, fake, C.c_size_t(8), None) == -4
