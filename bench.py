@@ -207,6 +207,12 @@ def main():
                      "launch_ms": mean_ms["ffn"]},
     }
 
+    # what this machine sustains, next to the nominal peaks: MFMA-only loop (no memory instruction) with zero
+    # and with random bf16 operands, and a plain streaming copy
+    result["roofline"]["peak_measured"] = measure_peaks(torch, probe, dev)
+    result["roofline"]["frac_of_measured_mfma_random"] = (
+        ffn_tflops / result["roofline"]["peak_measured"]["mfma_only_random_operands_tflops"])
+
     if args.calibrate_copy:
         src = torch.ones((1 << 28,), dtype=torch.float32, device=dev)      # 1 GiB
         dst = torch.empty_like(src)
@@ -219,6 +225,35 @@ def main():
         result["cpu_baseline"] = cpu_baseline(cfg, xs[0], wg, biases[0], tpg, plans[0], host_w, slot_experts[0],
                                               args.cpu_sample_tokens)
     print(json.dumps(result), flush=True)
+
+
+def measure_peaks(torch, probe, dev):
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps
+    wgs, iters = 256, 20000
+    out = torch.empty((wgs * 512,), dtype=torch.float32, device=dev)
+    res = {}
+    for name, rnd in (("mfma_only_zero_operands_tflops", False), ("mfma_only_random_operands_tflops", True)):
+        flops = [0.0]
+        def run():
+            flops[0] = probe.peak_mfma(wgs, iters, rnd, out=out)
+        t = timed(run, 3)
+        res[name] = flops[0] / t / 1e12
+    src = torch.empty((1 << 28,), dtype=torch.float32, device=dev)          # 1 GiB read + 1 GiB write
+    dst = torch.empty_like(src)
+    src.fill_(1.0)
+    t = timed(lambda: dst.copy_(src), 5)
+    res["copy_read_plus_write_gbps"] = 2 * src.numel() * 4 / t / 1e9
+    del src, dst, out
+    return res
 
 
 def cpu_baseline(cfg, x, wg, bias, tpg, plan, host_w, slot_expert, sample_tokens):

@@ -59,8 +59,11 @@ def lib():
         L.probe_grouped_ffn.argtypes = ([C.c_void_p] * 4 + [C.c_int] * 4 + [C.c_void_p] * 2 +
                                         [C.c_size_t, C.c_void_p])
         L.probe_combine.argtypes = [C.c_void_p] * 3 + [C.c_int] * 3 + [C.c_void_p] * 2
+        L.probe_peak_mfma_flops_per_launch.restype = C.c_double
+        L.probe_peak_mfma_flops_per_launch.argtypes = [C.c_int, C.c_int]
+        L.probe_peak_mfma.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
         for name in ("probe_route_topk", "probe_predict_topk", "probe_permute", "probe_grouped_ffn",
-                     "probe_combine"):
+                     "probe_combine", "probe_peak_mfma"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -264,6 +267,15 @@ probe_predict_topk = predict_topk
 probe_permute = permute
 probe_grouped_ffn = grouped_ffn
 probe_combine = combine
+
+
+def peak_mfma(workgroups=256, iters=20000, random_operands=True, *, out=None, stream=None):
+    """probe_peak_mfma: launches the MFMA-only loop; returns the flops of the launch (time it with events)."""
+    if out is None:
+        out = torch.empty((workgroups * 512,), dtype=torch.float32, device="cuda")
+    _want(out, torch.float32, (workgroups * 512,), "out")
+    _check(lib().probe_peak_mfma(_ptr(out), workgroups, iters, 1 if random_operands else 0, _stream(stream)))
+    return float(lib().probe_peak_mfma_flops_per_launch(workgroups, iters))
 
 
 def version() -> str:
