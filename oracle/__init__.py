@@ -109,6 +109,21 @@ def predict_topk(h_prev_bits, w_gate_next, bias_next=None, tokens_per_group=None
                   tokens_per_group, k, renormalize)
 
 
+def predict_topk_residual(h_prev_bits, w_gate_next, bias_next, tokens_per_group, w1_hat_bits, w2_hat,
+                          k=2, renormalize=True):
+    """Eq. 7 in full: cloned router plus W2_hat silu(W1_hat h); w1_hat bf16 bits [D,H], w2_hat fp32 [E,D]."""
+    w1_hat_bits = _chk(w1_hat_bits, np.uint16)
+    w2_hat = _chk(w2_hat, np.float32)
+    D = w1_hat_bits.shape[0]
+    assert w1_hat_bits.shape == (D, h_prev_bits.shape[1]) and w2_hat.shape == (w_gate_next.shape[0], D)
+    fn = _load().oracle_predict_topk_residual
+
+    def bound(*a):
+        # a = (x, w_gate, bias, G, tpg, T, H, E, k, renorm, outputs...): insert the residual after tpg
+        return fn(*a[:5], _p(w1_hat_bits, C.c_uint16), _p(w2_hat, C.c_float), D, *a[5:])
+    return _route(bound, h_prev_bits, w_gate_next, bias_next, tokens_per_group, k, renormalize)
+
+
 def permute(topk_idx, rep_off, rep_slot, rep_weight, num_slots, x_bits=None):
     """Sequential weighted round-robin assignment and stable grouping by slot."""
     topk_idx = _chk(topk_idx, np.int32)

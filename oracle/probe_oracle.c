@@ -15,6 +15,9 @@
  *                         k largest; Table 1: n_e with sum_e n_e = B*k.
  *   oracle_predict_topk - Eq. 7 (gate-initialised lookahead predictor) with the residual at
  *                         its zero initialisation: the cloned router applied to h_{L-1}.
+ *   oracle_predict_topk_residual - Eq. 7 in full: frozen prior + W2_hat silu(W1_hat h).  The
+ *                         paper gives neither the hidden width nor the storage types of the
+ *                         residual; here W1_hat is bf16 [D,H], W2_hat fp32 [E,D], no biases.
  *   oracle_permute      - token assignment A of Sec. 3.1 / Sec. 4.3: sum_r n_{e,r} = n_e and
  *                         n_{e,r} > 0 => P_{r,e} = 1, applied by weighted round-robin in
  *                         arrival order (a reading; the paper does not fix the rule).
@@ -27,7 +30,9 @@
  * Pins (tests/test_oracle_*.py): brute-force stable sort top-k, the Zipf closed form of a
  * bias-only softmax, uniform case and tie-break, torch fp64 library cross-checks, permutation
  * invariants and a hand-worked 6-token example, the closed-form per-replica counts,
- * identity-expert combine, plan invariance of the whole layer.
+ * identity-expert combine, plan invariance of the whole layer; for the residual: W2_hat = 0
+ * gives the router bit for bit, a one-hot construction with a closed form, additivity in
+ * W2_hat of the logits, and a torch fp64 cross-check.
  */
 #include <math.h>
 #ifdef _OPENMP
@@ -53,12 +58,20 @@ static double bf16_to_double(uint16_t v) {
  * outputs: logits [T,E] f64, probs [T,E] f64, idx [T,k] i32, w [T,k] f64,
  *          counts [E] i32.  Any output pointer may be NULL.
  */
-int oracle_route_topk(const uint16_t* x, const float* w_gate, const float* bias,
-                      int G, int tokens_per_group, int T, int H, int E, int k,
+/*
+ * Shared body of the router and of the predictor.  With w1_hat == NULL the logits are
+ * W h + b; otherwise the residual of Eq. 7 is added:
+ *     l = W h + b + W2_hat silu(W1_hat h),   silu(u) = u / (1 + exp(-u))
+ *   w1_hat  [D,H] bf16 bit patterns,  w2_hat  [E,D] fp32.
+ */
+static int route_body(const uint16_t* x, const float* w_gate, const float* bias,
+                      int G, int tokens_per_group, const uint16_t* w1_hat, const float* w2_hat,
+                      int D, int T, int H, int E, int k,
                       int renormalize, double* logits_out, double* probs_out,
                       int32_t* idx_out, double* w_out, int32_t* counts_out) {
   if (T < 0 || H <= 0 || E <= 0 || k <= 0 || k > E) return -1;
   if (bias && (G < 1 || tokens_per_group < 1)) return -1;
+  if (w1_hat && (!w2_hat || D <= 0)) return -1;
   int32_t* idx_tmp = (int32_t*)malloc(sizeof(int32_t) * (size_t)(T > 0 ? T : 1) * k);
   if (!idx_tmp) return -2;
 
@@ -79,6 +92,22 @@ int oracle_route_topk(const uint16_t* x, const float* w_gate, const float* bias,
         acc += (double)w_gate[(size_t)e * H + h] * bf16_to_double(x[(size_t)t * H + h]);
       if (bias) acc += (double)bias[(size_t)g * E + e];
       l[e] = acc;
+    }
+    if (w1_hat) {
+      /* trainable residual: s = silu(W1_hat h), l_e += sum_d W2_hat[e,d] s_d */
+      double* sv = (double*)malloc(sizeof(double) * D);
+      for (int d = 0; d < D; ++d) {
+        double u = 0.0;
+        for (int h = 0; h < H; ++h)
+          u += bf16_to_double(w1_hat[(size_t)d * H + h]) * bf16_to_double(x[(size_t)t * H + h]);
+        sv[d] = u / (1.0 + exp(-u));
+      }
+      for (int e = 0; e < E; ++e) {
+        double r = 0.0;
+        for (int d = 0; d < D; ++d) r += (double)w2_hat[(size_t)e * D + d] * sv[d];
+        l[e] += r;
+      }
+      free(sv);
     }
     /* softmax over all E experts */
     double m = l[0];
@@ -123,14 +152,34 @@ int oracle_route_topk(const uint16_t* x, const float* w_gate, const float* bias,
   return 0;
 }
 
+int oracle_route_topk(const uint16_t* x, const float* w_gate, const float* bias,
+                      int G, int tokens_per_group, int T, int H, int E, int k,
+                      int renormalize, double* logits_out, double* probs_out,
+                      int32_t* idx_out, double* w_out, int32_t* counts_out) {
+  return route_body(x, w_gate, bias, G, tokens_per_group, NULL, NULL, 0, T, H, E, k, renormalize,
+                    logits_out, probs_out, idx_out, w_out, counts_out);
+}
+
 /* Eq. 7 with the trainable residual at its zero initialisation: the frozen prior only. */
 int oracle_predict_topk(const uint16_t* h_prev, const float* w_gate_next,
                         const float* bias_next, int G, int tokens_per_group, int T, int H,
                         int E, int k, int renormalize, double* logits_out,
                         double* probs_out, int32_t* idx_out, double* w_out,
                         int32_t* nhat_out) {
-  return oracle_route_topk(h_prev, w_gate_next, bias_next, G, tokens_per_group, T, H, E, k,
-                           renormalize, logits_out, probs_out, idx_out, w_out, nhat_out);
+  return route_body(h_prev, w_gate_next, bias_next, G, tokens_per_group, NULL, NULL, 0, T, H, E, k,
+                    renormalize, logits_out, probs_out, idx_out, w_out, nhat_out);
+}
+
+/* Eq. 7 in full: frozen prior plus the residual MLP (hidden width D, SiLU, no biases). */
+int oracle_predict_topk_residual(const uint16_t* h_prev, const float* w_gate_next,
+                                 const float* bias_next, int G, int tokens_per_group,
+                                 const uint16_t* w1_hat, const float* w2_hat, int D, int T, int H,
+                                 int E, int k, int renormalize, double* logits_out,
+                                 double* probs_out, int32_t* idx_out, double* w_out,
+                                 int32_t* nhat_out) {
+  if (!w1_hat || !w2_hat || D <= 0) return -1;
+  return route_body(h_prev, w_gate_next, bias_next, G, tokens_per_group, w1_hat, w2_hat, D, T, H,
+                    E, k, renormalize, logits_out, probs_out, idx_out, w_out, nhat_out);
 }
 
 /* --------------------------------------------------------------- permute ---- */

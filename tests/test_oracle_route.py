@@ -144,3 +144,77 @@ def test_imbalance_ratio_eq1(oracle):
     assert oracle.imbalance_ratio(np.array([5.0, 5.0, 5.0, 5.0])) == 1.0
     assert oracle.imbalance_ratio(np.array([8.0, 0.0, 0.0, 0.0])) == 4.0
     assert abs(oracle.imbalance_ratio(np.array([3.0, 1.0])) - 1.5) < 1e-15
+
+
+# ---------------------------------------------------------------- Eq. 7 with its residual
+
+def test_residual_with_zero_output_layer_is_the_router(oracle):
+    """Eq. 7 at the initialisation the paper prescribes (W2_hat = 0): logits, order and weights of the router."""
+    T, H, E, D = 40, 32, 12, 24
+    x, w, b = _rand_case(70, T, H, E)
+    rng = np.random.default_rng(71)
+    w1 = wl.f32_to_bf16_bits(rng.standard_normal((D, H), dtype=np.float32))
+    w2 = np.zeros((E, D), np.float32)
+    r = oracle.route_topk(x, w, b, k=3)
+    p = oracle.predict_topk_residual(x, w, b, None, w1, w2, k=3)
+    np.testing.assert_array_equal(p["logits"], r["logits"])
+    np.testing.assert_array_equal(p["idx"], r["idx"])
+    np.testing.assert_array_equal(p["w"], r["w"])
+
+
+def test_residual_one_hot_closed_form(oracle):
+    """W1_hat picks one coordinate of h, W2_hat sends it to one expert: exactly one logit moves, by
+    c * silu(h_j).  silu(1) = 0.7310585786300049 and silu(-2) = -0.2384058440442351 are typed in.
+    H, D and E all differ and the ones sit off the diagonal, so a transposed operand moves another
+    logit or another token."""
+    T, H, E, D = 2, 5, 7, 3
+    xf = np.zeros((T, H), np.float32)
+    xf[0, 2], xf[1, 2] = 1.0, -2.0
+    xf[0, 4], xf[1, 0] = 0.5, 3.0            # coordinates the residual must ignore
+    x = wl.f32_to_bf16_bits(xf)
+    w = np.zeros((E, H), np.float32)
+    w1f = np.zeros((D, H), np.float32)
+    w1f[1, 2] = 1.0
+    w2 = np.zeros((E, D), np.float32)
+    w2[3, 1] = 2.0
+    p = oracle.predict_topk_residual(x, w, None, None, wl.f32_to_bf16_bits(w1f), w2, k=1)
+    want = np.zeros((T, E))
+    want[0, 3] = 2.0 * 0.7310585786300049
+    want[1, 3] = 2.0 * -0.2384058440442351
+    np.testing.assert_allclose(p["logits"], want, rtol=0, atol=1e-15)
+    assert p["idx"][0, 0] == 3                       # raised logit wins
+    assert p["idx"][1, 0] == 0                       # lowered logit loses to the tie at 0, lowest index
+
+
+def test_residual_is_additive_in_the_output_layer(oracle):
+    """The logits are affine in W2_hat: the shift from W2a + W2b is the sum of the two shifts."""
+    T, H, E, D = 30, 48, 9, 16
+    x, w, b = _rand_case(72, T, H, E)
+    rng = np.random.default_rng(73)
+    w1 = wl.f32_to_bf16_bits(rng.standard_normal((D, H), dtype=np.float32) * np.float32(0.2))
+    # entries with few significant bits, so that W2a + W2b is exact in fp32
+    w2a = (rng.integers(-8, 9, (E, D)) / 16.0).astype(np.float32)
+    w2b = (rng.integers(-8, 9, (E, D)) / 16.0).astype(np.float32)
+    base = oracle.route_topk(x, w, b, k=2)["logits"]
+    la = oracle.predict_topk_residual(x, w, b, None, w1, w2a, k=2)["logits"] - base
+    lb = oracle.predict_topk_residual(x, w, b, None, w1, w2b, k=2)["logits"] - base
+    lab = oracle.predict_topk_residual(x, w, b, None, w1, w2a + w2b, k=2)["logits"] - base
+    np.testing.assert_allclose(lab, la + lb, rtol=0, atol=1e-11)
+    assert np.abs(la).max() > 0.1                    # the residual is not trivially zero here
+
+
+def test_residual_matches_torch_fp64(oracle):
+    """Library cross-check: torch matmul + torch.nn.functional.silu in fp64."""
+    T, H, E, D = 25, 40, 11, 20
+    x, w, b = _rand_case(74, T, H, E)
+    rng = np.random.default_rng(75)
+    w1 = wl.f32_to_bf16_bits(rng.standard_normal((D, H), dtype=np.float32) * np.float32(0.3))
+    w2 = rng.standard_normal((E, D)).astype(np.float32)
+    p = oracle.predict_topk_residual(x, w, b, None, w1, w2, k=4)
+    h = torch.from_numpy(wl.bf16_bits_to_f32(x).astype(np.float64))
+    l = h @ torch.from_numpy(w.astype(np.float64)).T + torch.from_numpy(b.astype(np.float64))
+    l = l + torch.nn.functional.silu(h @ torch.from_numpy(wl.bf16_bits_to_f32(w1).astype(np.float64)).T) \
+        @ torch.from_numpy(w2.astype(np.float64)).T
+    np.testing.assert_allclose(p["logits"], l.numpy(), rtol=0, atol=1e-11)
+    np.testing.assert_allclose(p["probs"], torch.softmax(l, 1).numpy(), rtol=0, atol=1e-13)
+    assert p["counts"].sum() == T * 4
