@@ -7,7 +7,8 @@
  * auxiliary track (Sec. 4.2):
  *
  *   probe_route_topk    router of layer L: logits W_L h + b_L, softmax, k largest
- *   probe_predict_topk  gate-initialised lookahead predictor (Eq. 7, frozen prior term)
+ *   probe_predict_topk  gate-initialised lookahead predictor (Eq. 7, frozen prior term);
+ *                       probe_predict_topk_residual adds the trainable residual MLP of Eq. 7
  *   probe_permute       group (token, top-k position) pairs by the expert replica that the
  *                       balance plan (placement P, assignment A; Sec. 3.1, Sec. 4.3) gives them
  *   probe_grouped_ffn   grouped SwiGLU expert FFN over native + replicated experts
@@ -56,6 +57,7 @@ extern "C" {
 #define PROBE_MAX_EXPERTS 256  /* E                         */
 #define PROBE_MAX_TOPK      8  /* k                         */
 #define PROBE_MAX_SLOTS  1024  /* S                         */
+#define PROBE_MAX_RESIDUAL_WIDTH 1024 /* D of the predictor's residual MLP */
 
 /* Text of the last error raised on the calling thread ("" if none). Host pointer, owned by
  * the library, valid until the next failing call on the same thread. */
@@ -107,6 +109,23 @@ int probe_predict_topk(const void* h_prev_bf16, const float* w_gate_next,
                        int H, int E, int k, int renormalize, int32_t* pred_idx, float* pred_w,
                        float* probs, int32_t* pred_counts, void* workspace,
                        size_t workspace_bytes, void* stream);
+
+/* Eq. 7 in full: pred_logits = W_L h + b_L + W2_hat silu(W1_hat h), silu(u) = u / (1 + exp(-u)),
+ * then softmax / top-k / counts exactly as above.  The paper fixes neither the hidden width D of
+ * the residual MLP nor how its weights are stored; here
+ *   w1_hat_bf16  device, bf16 [D,H]  (first layer, no bias)
+ *   w2_hat       device, fp32 [E,D]  (second layer, no bias; all zeros = probe_predict_topk)
+ * u is accumulated in fp32 from exact bf16 x bf16 products on the matrix cores, silu and the second
+ * layer run in fp32.  Other arguments and limits as probe_route_topk; D % 8 == 0, D <= 1024.
+ */
+size_t probe_predict_topk_residual_workspace_bytes(int T, int H, int E, int k, int D);
+
+int probe_predict_topk_residual(const void* h_prev_bf16, const float* w_gate_next,
+                                const float* bias_next, int bias_groups, int tokens_per_group,
+                                const void* w1_hat_bf16, const float* w2_hat, int D, int T, int H,
+                                int E, int k, int renormalize, int32_t* pred_idx, float* pred_w,
+                                float* probs, int32_t* pred_counts, void* workspace,
+                                size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------- permute ---
  *

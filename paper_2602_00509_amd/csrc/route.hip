@@ -44,12 +44,13 @@ __global__ __launch_bounds__(256) void gate_split_kernel(const float* __restrict
 }
 
 // ---- 2. gemm --------------------------------------------------------------------------
+template <int PL>
 __global__ __launch_bounds__(256, 2) void gate_gemm_kernel(const bf16_t* __restrict__ x,
                                                            const bf16_t* __restrict__ planes,
                                                            int T, int H, int E, int k_chunk,
                                                            float* __restrict__ partial) {
   __shared__ u32x4 sA[GBM * 8];
-  __shared__ u32x4 sB[3][GBN * 8];
+  __shared__ u32x4 sB[PL][GBN * 8];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int wm = wv >> 1, wn = wv & 1;
   const int m0 = blockIdx.x * GBM, n0 = blockIdx.y * GBN, ks = blockIdx.z;
@@ -64,7 +65,7 @@ __global__ __launch_bounds__(256, 2) void gate_gemm_kernel(const bf16_t* __restr
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  u32x4 ra[4], rb[3][4];
+  u32x4 ra[4], rb[PL][4];
   auto gload = [&](int k0) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -76,7 +77,7 @@ __global__ __launch_bounds__(256, 2) void gate_gemm_kernel(const bf16_t* __restr
       ra[j] = u32x4{0u, 0u, 0u, 0u};
       if (kin && grow < T) ra[j] = *reinterpret_cast<const u32x4*>(x + static_cast<long>(grow) * H + kk);
 #pragma unroll
-      for (int p = 0; p < 3; ++p) {
+      for (int p = 0; p < PL; ++p) {
         rb[p][j] = u32x4{0u, 0u, 0u, 0u};
         if (kin && brow < E)
           rb[p][j] = *reinterpret_cast<const u32x4*>(planes + p * plane_elems + static_cast<long>(brow) * H + kk);
@@ -90,7 +91,7 @@ __global__ __launch_bounds__(256, 2) void gate_gemm_kernel(const bf16_t* __restr
       int row = idx >> 3, c = idx & 7;
       sA[lds_chunk_off(row, c)] = ra[j];
 #pragma unroll
-      for (int p = 0; p < 3; ++p) sB[p][lds_chunk_off(row, c)] = rb[p][j];
+      for (int p = 0; p < PL; ++p) sB[p][lds_chunk_off(row, c)] = rb[p][j];
     }
   };
 
@@ -109,7 +110,7 @@ __global__ __launch_bounds__(256, 2) void gate_gemm_kernel(const bf16_t* __restr
 #pragma unroll
       for (int mi = 0; mi < 2; ++mi) a[mi] = sA[lds_chunk_off(64 * wm + 32 * mi + (lane & 31), c)];
 #pragma unroll
-      for (int p = 2; p >= 0; --p) {
+      for (int p = PL - 1; p >= 0; --p) {
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni) {
           u32x4 b = sB[p][lds_chunk_off(64 * wn + 32 * ni + (lane & 31), c)];
@@ -147,7 +148,7 @@ __global__ __launch_bounds__(256, 2) void gate_gemm_kernel(const bf16_t* __restr
 // moves a third less operand data per MFMA and is used for large batches.
 constexpr int kGateLdsBytes = 2 * (256 + 384) * 128;
 
-template <int MI>
+template <int MI, int PL>
 __global__ __launch_bounds__(512, 2) void gate_gemm_dma_kernel(const bf16_t* __restrict__ x,
                                                                const bf16_t* __restrict__ planes,
                                                                int T, int H, int E, int k_chunk,
@@ -162,17 +163,17 @@ __global__ __launch_bounds__(512, 2) void gate_gemm_dma_kernel(const bf16_t* __r
   if (klen <= 0) return;
   const int rows = T - m0;
   __amdgpu_buffer_rsrc_t rA = make_rsrc(x + static_cast<size_t>(m0) * H, static_cast<size_t>(rows) * H * 2);
-  __amdgpu_buffer_rsrc_t rB = make_rsrc(planes, static_cast<size_t>(3) * E * H * 2);
-  int voff[MI + 6];
+  __amdgpu_buffer_rsrc_t rB = make_rsrc(planes, static_cast<size_t>(PL) * E * H * 2);
+  int voff[MI + 2 * PL];
   dma_offsets<MI>(wv, lane, H * 2, [&](int r) { return min(r, rows - 1); }, voff);
   // B-tile row j: plane j / 128, expert n0 + j % 128 (clamped; columns past E are masked at the store)
-  dma_offsets<6>(wv, lane, H * 2, [&](int j) { return (j >> 7) * E + min(n0 + (j & 127), E - 1); }, voff + MI);
+  dma_offsets<2 * PL>(wv, lane, H * 2, [&](int j) { return (j >> 7) * E + min(n0 + (j & 127), E - 1); }, voff + MI);
   f32x16 acc[MI][1];
 #pragma unroll
   for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[i][0][r] = 0.f;
-  gemm_mainloop<MI, 1, 3, 2>(rA, rB, voff, kbeg, klen, smem, wv, lane, acc);
+  gemm_mainloop<MI, 1, PL, 2>(rA, rB, voff, kbeg, klen, smem, wv, lane, acc);
 
   const bool vec = (E & 3) == 0;
 #pragma unroll
@@ -208,11 +209,13 @@ static int gate_prepare() {
   }
   std::lock_guard<std::mutex> lock(mu);
   if (done[dev]) return PROBE_OK;
-  hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(gate_gemm_dma_kernel<2>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kGateLdsBytes);
-  if (err == hipSuccess)
-    err = hipFuncSetAttribute(reinterpret_cast<const void*>(gate_gemm_dma_kernel<4>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, kGateLdsBytes);
+  hipError_t err = hipSuccess;
+  const void* kernels[4] = {reinterpret_cast<const void*>(gate_gemm_dma_kernel<2, 3>),
+                            reinterpret_cast<const void*>(gate_gemm_dma_kernel<4, 3>),
+                            reinterpret_cast<const void*>(gate_gemm_dma_kernel<2, 1>),
+                            reinterpret_cast<const void*>(gate_gemm_dma_kernel<4, 1>)};
+  for (int i = 0; i < 4 && err == hipSuccess; ++i)
+    err = hipFuncSetAttribute(kernels[i], hipFuncAttributeMaxDynamicSharedMemorySize, kGateLdsBytes);
   if (err != hipSuccess) {
     set_error("probe_route_topk: cannot reserve %d bytes of LDS: %s", kGateLdsBytes, hipGetErrorString(err));
     return PROBE_EHIP;
@@ -453,8 +456,55 @@ __global__ __launch_bounds__(256) void gate_softmax_topk_kernel(
   if (counts && tid < E && hist[tid] != 0) atomicAdd(&counts[tid], hist[tid]);
 }
 
+// ---- 4. residual of the predictor (Eq. 7) ------------------------------------------------
+// r[t,e] = sum_d w2_hat[e,d] * silu(u[t,d]),  u = W1_hat h summed over its split-K partials, all in
+// fp32 with fixed summation order.  One workgroup takes 16 tokens: their silu(u) rows go to LDS,
+// then thread e walks row e of w2_hat once and accumulates the 16 tokens side by side (the LDS
+// reads are broadcasts).  r is written as one more "partial" plane of the logits, so the
+// softmax / top-k kernel adds it like a split-K slice.
+constexpr int kResidTokens = 16;
+
+__global__ __launch_bounds__(256) void predictor_residual_kernel(const float* __restrict__ upartial, int KS2,
+                                                                 const float* __restrict__ w2_hat, int T,
+                                                                 int D, int E, float* __restrict__ r_plane) {
+  extern __shared__ float s_silu[];  // [kResidTokens][D]
+  const int tid = threadIdx.x;
+  const int t0 = blockIdx.x * kResidTokens;
+  for (int idx = tid; idx < kResidTokens * D; idx += 256) {
+    const int t = idx / D, d = idx - t * D;
+    float v = 0.f;
+    if (t0 + t < T) {
+      float u = 0.f;
+      for (int q = 0; q < KS2; ++q) u += upartial[(static_cast<long>(q) * T + t0 + t) * D + d];
+      v = u / (1.f + expf(-u));
+    }
+    s_silu[idx] = v;
+  }
+  __syncthreads();
+  if (tid >= E) return;
+  float acc[kResidTokens];
+#pragma unroll
+  for (int t = 0; t < kResidTokens; ++t) acc[t] = 0.f;
+  const float4* wrow = reinterpret_cast<const float4*>(w2_hat + static_cast<long>(tid) * D);
+  for (int d4 = 0; d4 < D / 4; ++d4) {
+    const float4 w = wrow[d4];
+#pragma unroll
+    for (int t = 0; t < kResidTokens; ++t) {
+      const float4 sv = *reinterpret_cast<const float4*>(s_silu + t * D + 4 * d4);
+      acc[t] = fmaf(w.x, sv.x, acc[t]);
+      acc[t] = fmaf(w.y, sv.y, acc[t]);
+      acc[t] = fmaf(w.z, sv.z, acc[t]);
+      acc[t] = fmaf(w.w, sv.w, acc[t]);
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < kResidTokens; ++t)
+    if (t0 + t < T) r_plane[static_cast<long>(t0 + t) * E + tid] = acc[t];
+}
+
 struct RouteShape {
-  int bm;  // tokens per workgroup of the gemm (128 or 256)
+  bool dma;  // H % 64 == 0: the DMA-to-LDS pipeline; otherwise the register-staged kernel
+  int bm;    // tokens per workgroup of the gemm (128 or 256)
   int mt, nt, ks, k_chunk;
   size_t planes_bytes, partial_bytes;
 };
@@ -463,9 +513,9 @@ static RouteShape route_shape(int T, int H, int E) {
   RouteShape s;
   // 256-token tiles when a split of 8 or less still gives every CU a workgroup; they aim at one
   // workgroup per CU (fewer, longer K ranges and half the partial sums), 128-token tiles at two
-  const bool dma = H % 64 == 0 && static_cast<size_t>(3) * E * H * 2 <= 0x7fffffffull;
+  s.dma = H % 64 == 0 && static_cast<size_t>(3) * E * H * 2 <= 0x7fffffffull;
   s.nt = (E + GBN - 1) / GBN;
-  s.bm = (dma && static_cast<long>((T + 255) / 256) * s.nt * 8 >= 256) ? 256 : GBM;
+  s.bm = (s.dma && static_cast<long>((T + 255) / 256) * s.nt * 8 >= 256) ? 256 : GBM;
   s.mt = (T + s.bm - 1) / s.bm;
   int tiles = s.mt * s.nt;
   int ksteps = (H + GBK - 1) / GBK;
@@ -481,10 +531,51 @@ static RouteShape route_shape(int T, int H, int E) {
   return s;
 }
 
+// x [T,H] times a stack of PL bf16 planes [PL][N][H] -> partial [ks][T][N] fp32
+template <int PL>
+static void launch_gate_gemm(const RouteShape& sh, hipStream_t st, const bf16_t* x, const bf16_t* planes, int T,
+                             int H, int N, float* partial) {
+  if (sh.dma) {
+    const int lds = 2 * (sh.bm + 128 * PL) * 128;
+    if (sh.bm == 256)
+      hipLaunchKernelGGL((gate_gemm_dma_kernel<4, PL>), dim3(sh.mt, sh.nt, sh.ks), dim3(512), lds, st, x, planes, T,
+                         H, N, sh.k_chunk, partial);
+    else
+      hipLaunchKernelGGL((gate_gemm_dma_kernel<2, PL>), dim3(sh.mt, sh.nt, sh.ks), dim3(512), lds, st, x, planes, T,
+                         H, N, sh.k_chunk, partial);
+  } else {
+    hipLaunchKernelGGL(gate_gemm_kernel<PL>, dim3(sh.mt, sh.nt, sh.ks), dim3(256), 0, st, x, planes, T, H, N,
+                       sh.k_chunk, partial);
+  }
+}
+
+// Workspace of a call: gate planes | logit partials (+ one plane for the residual) | u partials
+struct RouteLayout {
+  RouteShape gate, resid;
+  size_t partial_bytes, upartial_bytes, total;
+};
+
+static RouteLayout route_layout(int T, int H, int E, int D) {
+  RouteLayout L;
+  L.gate = route_shape(T, H, E);
+  const size_t plane = static_cast<size_t>(T > 0 ? T : 1) * E * sizeof(float);
+  L.partial_bytes = align_up((L.gate.ks + (D > 0 ? 1 : 0)) * plane, 256);
+  L.upartial_bytes = 0;
+  if (D > 0) {
+    L.resid = route_shape(T, H, D);
+    L.upartial_bytes = L.resid.partial_bytes;
+  }
+  L.total = L.gate.planes_bytes + L.partial_bytes + L.upartial_bytes;
+  return L;
+}
+
+// Router (w1_hat == nullptr) or predictor with the residual MLP of Eq. 7 (w1_hat bf16 [D,H],
+// w2_hat fp32 [E,D]).
 static int route_impl(const char* name, const void* x_bf16, const float* w_gate, const float* bias,
-                      int bias_groups, int tokens_per_group, int T, int H, int E, int k,
-                      int renormalize, int32_t* topk_idx, float* topk_w, float* probs,
-                      int32_t* expert_counts, void* workspace, size_t workspace_bytes, void* stream) {
+                      int bias_groups, int tokens_per_group, const void* w1_hat, const float* w2_hat, int D,
+                      int T, int H, int E, int k, int renormalize, int32_t* topk_idx, float* topk_w,
+                      float* probs, int32_t* expert_counts, void* workspace, size_t workspace_bytes,
+                      void* stream) {
   PROBE_REQUIRE(T >= 0 && H > 0 && E > 0 && k > 0 && k <= E, PROBE_EINVAL,
                 "%s: bad dims T=%d H=%d E=%d k=%d", name, T, H, E, k);
   PROBE_REQUIRE(bias == nullptr || (bias_groups >= 1 && tokens_per_group >= 1), PROBE_EINVAL,
@@ -496,39 +587,48 @@ static int route_impl(const char* name, const void* x_bf16, const float* w_gate,
   PROBE_REQUIRE(T == 0 || (x_bf16 && topk_idx && topk_w), PROBE_EINVAL, "%s: null pointer", name);
   PROBE_REQUIRE(aligned16(x_bf16) && aligned16(w_gate), PROBE_EALIGN,
                 "%s: x and w_gate must be 16-byte aligned", name);
-  RouteShape sh = route_shape(T, H, E);
-  PROBE_REQUIRE(workspace && aligned16(workspace) && workspace_bytes >= sh.planes_bytes + sh.partial_bytes,
-                PROBE_EWORKSPACE, "%s: workspace too small or misaligned (%zu < %zu)", name,
-                workspace_bytes, sh.planes_bytes + sh.partial_bytes);
-  if (T > 0 && H % 64 == 0 && static_cast<size_t>(3) * E * H * 2 <= 0x7fffffffull) {
+  const bool resid = D > 0;
+  if (resid) {
+    PROBE_REQUIRE(w1_hat && w2_hat, PROBE_EINVAL, "%s: residual weights are NULL", name);
+    PROBE_REQUIRE(D % 8 == 0 && D <= PROBE_MAX_RESIDUAL_WIDTH, PROBE_EUNSUPPORTED,
+                  "%s: needs D %% 8 == 0 and D <= %d (D=%d)", name, PROBE_MAX_RESIDUAL_WIDTH, D);
+    PROBE_REQUIRE(aligned16(w1_hat) && aligned16(w2_hat), PROBE_EALIGN,
+                  "%s: w1_hat and w2_hat must be 16-byte aligned", name);
+  }
+  RouteLayout L = route_layout(T, H, E, resid ? D : 0);
+  const RouteShape& sh = L.gate;
+  PROBE_REQUIRE(workspace && aligned16(workspace) && workspace_bytes >= L.total, PROBE_EWORKSPACE,
+                "%s: workspace too small or misaligned (%zu < %zu)", name, workspace_bytes, L.total);
+  if (T > 0 && (sh.dma || (resid && L.resid.dma))) {
     int rc = gate_prepare();
     if (rc != PROBE_OK) return rc;
   }
   hipStream_t st = static_cast<hipStream_t>(stream);
+  const bf16_t* x = static_cast<const bf16_t*>(x_bf16);
   bf16_t* planes = static_cast<bf16_t*>(workspace);
   float* partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + sh.planes_bytes);
+  float* upartial = reinterpret_cast<float*>(static_cast<char*>(workspace) + sh.planes_bytes + L.partial_bytes);
   long n = static_cast<long>(E) * H;
   if (T == 0) n = 0;  // nothing to route: only the counts are cleared
   long split_threads = n > E ? n : E;
   hipLaunchKernelGGL(gate_split_kernel, dim3(static_cast<unsigned>((split_threads + 255) / 256)), dim3(256),
                      0, st, w_gate, n, planes, expert_counts, E);
   if (T > 0) {
-    if (H % 64 == 0 && static_cast<size_t>(3) * E * H * 2 <= 0x7fffffffull) {
-      if (sh.bm == 256)
-        hipLaunchKernelGGL(gate_gemm_dma_kernel<4>, dim3(sh.mt, sh.nt, sh.ks), dim3(512), kGateLdsBytes, st,
-                           static_cast<const bf16_t*>(x_bf16), planes, T, H, E, sh.k_chunk, partial);
-      else
-        hipLaunchKernelGGL(gate_gemm_dma_kernel<2>, dim3(sh.mt, sh.nt, sh.ks), dim3(512), kGateLdsBytes, st,
-                           static_cast<const bf16_t*>(x_bf16), planes, T, H, E, sh.k_chunk, partial);
-    } else {
-      hipLaunchKernelGGL(gate_gemm_kernel, dim3(sh.mt, sh.nt, sh.ks), dim3(256), 0, st,
-                         static_cast<const bf16_t*>(x_bf16), planes, T, H, E, sh.k_chunk, partial);
+    launch_gate_gemm<3>(sh, st, x, planes, T, H, E, partial);
+    int planes_to_sum = sh.ks;
+    if (resid) {
+      // u = W1_hat h (one bf16 plane), then r = W2_hat silu(u) as one more plane of the logits
+      launch_gate_gemm<1>(L.resid, st, x, static_cast<const bf16_t*>(w1_hat), T, H, D, upartial);
+      hipLaunchKernelGGL(predictor_residual_kernel, dim3((T + kResidTokens - 1) / kResidTokens), dim3(256),
+                         kResidTokens * D * sizeof(float), st, upartial, L.resid.ks, w2_hat, T, D, E,
+                         partial + static_cast<size_t>(sh.ks) * T * E);
+      planes_to_sum = sh.ks + 1;
     }
     int grid = (T + 31) / 32;
     if (grid > 4096) grid = 4096;
     int G = bias ? bias_groups : 1, tpg = bias ? tokens_per_group : 1;
-#define PROBE_TOPK_LAUNCH(V)                                                                           \
-  hipLaunchKernelGGL(gate_softmax_topk_kernel<V>, dim3(grid), dim3(256), 0, st, partial, sh.ks, bias, \
+#define PROBE_TOPK_LAUNCH(V)                                                                               \
+  hipLaunchKernelGGL(gate_softmax_topk_kernel<V>, dim3(grid), dim3(256), 0, st, partial, planes_to_sum, bias, \
                      G, tpg, T, E, k, renormalize ? 1 : 0, topk_idx, topk_w, probs, expert_counts)
     if (E <= 64) {
       PROBE_TOPK_LAUNCH(1);
@@ -547,12 +647,17 @@ static int route_impl(const char* name, const void* x_bf16, const float* w_gate,
 extern "C" size_t probe_route_topk_workspace_bytes(int T, int H, int E, int k) {
   (void)k;
   if (T < 0 || H <= 0 || E <= 0) return 0;
-  probe::RouteShape s = probe::route_shape(T, H, E);
-  return s.planes_bytes + s.partial_bytes;
+  return probe::route_layout(T, H, E, 0).total;
 }
 
 extern "C" size_t probe_predict_topk_workspace_bytes(int T, int H, int E, int k) {
   return probe_route_topk_workspace_bytes(T, H, E, k);
+}
+
+extern "C" size_t probe_predict_topk_residual_workspace_bytes(int T, int H, int E, int k, int D) {
+  (void)k;
+  if (T < 0 || H <= 0 || E <= 0 || D <= 0) return 0;
+  return probe::route_layout(T, H, E, D).total;
 }
 
 extern "C" int probe_route_topk(const void* x_bf16, const float* w_gate, const float* bias,
@@ -560,9 +665,9 @@ extern "C" int probe_route_topk(const void* x_bf16, const float* w_gate, const f
                                 int renormalize, int32_t* topk_idx, float* topk_w, float* probs,
                                 int32_t* expert_counts, void* workspace, size_t workspace_bytes,
                                 void* stream) {
-  return probe::route_impl("probe_route_topk", x_bf16, w_gate, bias, bias_groups, tokens_per_group, T,
-                           H, E, k, renormalize, topk_idx, topk_w, probs, expert_counts, workspace,
-                           workspace_bytes, stream);
+  return probe::route_impl("probe_route_topk", x_bf16, w_gate, bias, bias_groups, tokens_per_group, nullptr,
+                           nullptr, 0, T, H, E, k, renormalize, topk_idx, topk_w, probs, expert_counts,
+                           workspace, workspace_bytes, stream);
 }
 
 // Eq. 7 with the residual at its zero initialisation is the cloned router applied to the
@@ -573,6 +678,19 @@ extern "C" int probe_predict_topk(const void* h_prev_bf16, const float* w_gate_n
                                   float* pred_w, float* probs, int32_t* pred_counts, void* workspace,
                                   size_t workspace_bytes, void* stream) {
   return probe::route_impl("probe_predict_topk", h_prev_bf16, w_gate_next, bias_next, bias_groups,
-                           tokens_per_group, T, H, E, k, renormalize, pred_idx, pred_w, probs,
-                           pred_counts, workspace, workspace_bytes, stream);
+                           tokens_per_group, nullptr, nullptr, 0, T, H, E, k, renormalize, pred_idx, pred_w,
+                           probs, pred_counts, workspace, workspace_bytes, stream);
+}
+
+// Eq. 7 in full: the frozen prior plus W2_hat silu(W1_hat h).
+extern "C" int probe_predict_topk_residual(const void* h_prev_bf16, const float* w_gate_next,
+                                           const float* bias_next, int bias_groups, int tokens_per_group,
+                                           const void* w1_hat_bf16, const float* w2_hat, int D, int T, int H,
+                                           int E, int k, int renormalize, int32_t* pred_idx, float* pred_w,
+                                           float* probs, int32_t* pred_counts, void* workspace,
+                                           size_t workspace_bytes, void* stream) {
+  PROBE_REQUIRE(D > 0, PROBE_EINVAL, "probe_predict_topk_residual: D=%d", D);
+  return probe::route_impl("probe_predict_topk_residual", h_prev_bf16, w_gate_next, bias_next, bias_groups,
+                           tokens_per_group, w1_hat_bf16, w2_hat, D, T, H, E, k, renormalize, pred_idx, pred_w,
+                           probs, pred_counts, workspace, workspace_bytes, stream);
 }

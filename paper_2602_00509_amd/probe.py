@@ -54,6 +54,11 @@ def lib():
         route_args = ([C.c_void_p] * 3 + [C.c_int] * 7 + [C.c_void_p] * 5 + [C.c_size_t, C.c_void_p])
         L.probe_route_topk.argtypes = route_args
         L.probe_predict_topk.argtypes = route_args
+        L.probe_predict_topk_residual.argtypes = ([C.c_void_p] * 3 + [C.c_int] * 2 + [C.c_void_p] * 2 +
+                                                  [C.c_int] * 6 + [C.c_void_p] * 5 + [C.c_size_t, C.c_void_p])
+        L.probe_predict_topk_residual.restype = C.c_int
+        L.probe_predict_topk_residual_workspace_bytes.restype = C.c_size_t
+        L.probe_predict_topk_residual_workspace_bytes.argtypes = [C.c_int] * 5
         L.probe_permute.argtypes = ([C.c_void_p, C.POINTER(_Plan), C.c_void_p] + [C.c_int] * 4 +
                                     [C.c_void_p] * 7 + [C.c_size_t, C.c_void_p])
         L.probe_grouped_ffn.argtypes = ([C.c_void_p] * 4 + [C.c_int] * 4 + [C.c_void_p] * 2 +
@@ -106,8 +111,12 @@ def route_topk_workspace_bytes(T, H, E, k):
 predict_topk_workspace_bytes = route_topk_workspace_bytes
 
 
+def predict_topk_residual_workspace_bytes(T, H, E, k, D):
+    return int(lib().probe_predict_topk_residual_workspace_bytes(T, H, E, k, D))
+
+
 def _route(fn, x, w_gate, bias, tokens_per_group, k, renormalize, want_probs, want_counts, out,
-           workspace, stream):
+           workspace, stream, residual=None):
     T, H = x.shape
     E = w_gate.shape[0]
     _want(x, torch.bfloat16, (T, H), "x")
@@ -133,11 +142,19 @@ def _route(fn, x, w_gate, bias, tokens_per_group, k, renormalize, want_probs, wa
     _want(out["w"], torch.float32, (T, k), "w")
     probs = out.get("probs") if want_probs else None
     counts = out.get("counts") if want_counts else None
-    nbytes = route_topk_workspace_bytes(T, H, E, k)
-    workspace = _ws(workspace, nbytes, dev)
-    rc = fn(_ptr(x), _ptr(w_gate), _ptr(bias), G, tpg, T, H, E, k, int(bool(renormalize)),
-            _ptr(out["idx"]), _ptr(out["w"]), _ptr(probs), _ptr(counts), _ptr(workspace),
-            workspace.numel(), _stream(stream))
+    tail = (T, H, E, k, int(bool(renormalize)), _ptr(out["idx"]), _ptr(out["w"]), _ptr(probs), _ptr(counts))
+    if residual is None:
+        workspace = _ws(workspace, route_topk_workspace_bytes(T, H, E, k), dev)
+        rc = fn(_ptr(x), _ptr(w_gate), _ptr(bias), G, tpg, *tail, _ptr(workspace), workspace.numel(),
+                _stream(stream))
+    else:
+        w1_hat, w2_hat = residual
+        D = w1_hat.shape[0]
+        _want(w1_hat, torch.bfloat16, (D, H), "w1_hat")
+        _want(w2_hat, torch.float32, (E, D), "w2_hat")
+        workspace = _ws(workspace, predict_topk_residual_workspace_bytes(T, H, E, k, D), dev)
+        rc = fn(_ptr(x), _ptr(w_gate), _ptr(bias), G, tpg, _ptr(w1_hat), _ptr(w2_hat), D, *tail,
+                _ptr(workspace), workspace.numel(), _stream(stream))
     _check(rc)
     return out
 
@@ -155,6 +172,14 @@ def predict_topk(h_prev, w_gate_next, bias_next=None, tokens_per_group=None, k=2
     """probe_predict_topk: lookahead predictor; ``counts`` is the predicted workload n-hat."""
     return _route(lib().probe_predict_topk, h_prev, w_gate_next, bias_next, tokens_per_group, k,
                   renormalize, want_probs, want_counts, out, workspace, stream)
+
+
+def predict_topk_residual(h_prev, w_gate_next, bias_next, tokens_per_group, w1_hat, w2_hat, k=2,
+                          renormalize=True, *, want_probs=False, want_counts=True, out=None,
+                          workspace=None, stream=None):
+    """probe_predict_topk_residual: Eq. 7 in full; w1_hat bf16 [D,H], w2_hat fp32 [E,D]."""
+    return _route(lib().probe_predict_topk_residual, h_prev, w_gate_next, bias_next, tokens_per_group, k,
+                  renormalize, want_probs, want_counts, out, workspace, stream, residual=(w1_hat, w2_hat))
 
 
 # ------------------------------------------------------------------------------ permute

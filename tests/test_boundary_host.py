@@ -67,6 +67,17 @@ def test_bad_arguments_are_rejected_without_a_launch(L):
         assert fn(fake, fake, None, 1, 1, 16, 64, 8, 2, 1, fake, fake, None, None, fake, C.c_size_t(16), None) == -4
         assert fn(fake, fake, fake, 0, 1, 16, 64, 8, 2, 1, fake, fake, None, None, fake, big, None) == -1    # G < 1
         assert "probe_" in err()
+    # predictor with its residual MLP
+    pr = L.probe_predict_topk_residual
+    ok_tail = (16, 64, 8, 2, 1, fake, fake, None, None, fake, big, None)
+    assert pr(fake, fake, None, 1, 1, fake, fake, 0, *ok_tail) == -1                  # D <= 0
+    assert pr(fake, fake, None, 1, 1, None, fake, 16, *ok_tail) == -1                 # w1_hat NULL
+    assert pr(fake, fake, None, 1, 1, fake, fake, 12, *ok_tail) == -2                 # D % 8
+    assert pr(fake, fake, None, 1, 1, fake, fake, 2048, *ok_tail) == -2               # D > 1024
+    assert pr(fake, fake, None, 1, 1, odd, fake, 16, *ok_tail) == -3
+    assert pr(fake, fake, None, 1, 1, fake, fake, 16, 16, 64, 8, 2, 1, fake, fake, None, None, fake,
+              C.c_size_t(L.probe_route_topk_workspace_bytes(16, 64, 8, 2)), None) == -4   # needs more than the router
+    assert L.probe_predict_topk_residual_workspace_bytes(16, 64, 8, 2, 16) > L.probe_route_topk_workspace_bytes(16, 64, 8, 2)
     # permute
     plan = _Plan(0x1000, 0x1000, 0x1000, 4)
     args = lambda **kw: None
