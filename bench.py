@@ -43,6 +43,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--config", type=int, default=3, help="benchmark configuration (1-5)")
     ap.add_argument("--batches", type=int, default=0, help="distinct batches to rotate over (0 = config default)")
+    ap.add_argument("--residual-width", type=int, default=0,
+                    help="width D of the predictor's residual MLP (Eq. 7); 0 = residual at its zero initialisation, "
+                         "i.e. probe_predict_topk")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -95,6 +98,12 @@ def main():
                       w=torch.empty((T, k), dtype=torch.float32, device=dev),
                       counts=torch.empty((E,), dtype=torch.int32, device=dev))
     ws_route = torch.empty(probe.route_topk_workspace_bytes(T, H, E, k), dtype=torch.uint8, device=dev)
+    D = args.residual_width
+    if D:
+        rng = np.random.default_rng(1000 + cfg.cid)
+        d_w1 = dev_bf16(wl.f32_to_bf16_bits(rng.standard_normal((D, H), dtype=np.float32) * np.float32(1.5 / np.sqrt(H))))
+        d_w2 = torch.from_numpy((rng.standard_normal((E, D)) * (0.3 / np.sqrt(D))).astype(np.float32)).to(dev)
+        ws_pred = torch.empty(probe.predict_topk_residual_workspace_bytes(T, H, E, k, D), dtype=torch.uint8, device=dev)
     ws_perm = torch.empty(max(256, probe.permute_workspace_bytes(T, E, k, S)), dtype=torch.uint8, device=dev)
     ws_ffn = torch.empty(probe.grouped_ffn_workspace_bytes(S, H, F, N), dtype=torch.uint8, device=dev)
     perm_out = dict(slot_counts=torch.empty((S,), dtype=torch.int32, device=dev),
@@ -130,7 +139,11 @@ def main():
             if ev is not None:
                 ev[i].record()
         mark(0)
-        probe.predict_topk(d_xs[b], d_wg_next, d_bias_next[b], tpg, k, True, out=p_out_pred, workspace=ws_route)
+        if D:
+            probe.predict_topk_residual(d_xs[b], d_wg_next, d_bias_next[b], tpg, d_w1, d_w2, k, True, out=p_out_pred,
+                                        workspace=ws_pred)
+        else:
+            probe.predict_topk(d_xs[b], d_wg_next, d_bias_next[b], tpg, k, True, out=p_out_pred, workspace=ws_route)
         mark(1)
         probe.route_topk(d_xs[b], d_wg, d_bias[b], tpg, k, True, out=r_out, workspace=ws_route)
         mark(2)
@@ -189,7 +202,8 @@ def main():
         "config": {"workload": "cfg%d %s: T=%d H=%d E=%d top-%d F=%d, %d native + %d replica slots, Zipf s=%.1f, "
                                "%d rotating batches" % (cfg.cid, cfg.name, T, H, E, k, F, cfg.E_loc, cfg.n_rep,
                                                         cfg.zipf_s, nb),
-                   "step": "predict_topk + route_topk + permute + grouped_ffn + combine",
+                   "step": ("predict_topk_residual(D=%d)" % D if D else "predict_topk") +
+                           " + route_topk + permute + grouped_ffn + combine",
                    "rows_per_step_mean": nl_mean, "active_slots_mean": act_mean},
         "stage_ms": mean_ms,
         "stage_ms_min": {n: float(np.min(v)) for n, v in stage_ms.items()},

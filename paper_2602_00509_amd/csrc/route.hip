@@ -458,48 +458,101 @@ __global__ __launch_bounds__(256) void gate_softmax_topk_kernel(
 
 // ---- 4. residual of the predictor (Eq. 7) ------------------------------------------------
 // r[t,e] = sum_d w2_hat[e,d] * silu(u[t,d]),  u = W1_hat h summed over its split-K partials, all in
-// fp32 with fixed summation order.  One workgroup takes 16 tokens: their silu(u) rows go to LDS,
-// then thread e walks row e of w2_hat once and accumulates the 16 tokens side by side (the LDS
-// reads are broadcasts).  r is written as one more "partial" plane of the logits, so the
-// softmax / top-k kernel adds it like a split-K slice.
-constexpr int kResidTokens = 16;
+// fp32 with fixed summation order.  One workgroup takes TOK tokens (32, 16 or 8 so that TOK * D <=
+// 8192): their silu(u) rows go to LDS; w2_hat passes through LDS in slices of 16 columns (coalesced
+// loads, the next slice in flight while the current one is consumed; row stride 20 words).  A thread
+// owns a register tile of 4 experts (lane, lane + 64, ...) x TOK/4 tokens (one token group per
+// wave), so that each 16-byte LDS read feeds several FMAs: the weight reads of sixteen lanes hit
+// sixteen different bank quads, the reads of silu(u) are broadcasts.  r is written as one more
+// "partial" plane of the logits, so the softmax / top-k kernel adds it like a split-K slice.
+constexpr int kResidSlice = 16, kResidStride = 20;
 
+template <int TOK>
 __global__ __launch_bounds__(256) void predictor_residual_kernel(const float* __restrict__ upartial, int KS2,
                                                                  const float* __restrict__ w2_hat, int T,
                                                                  int D, int E, float* __restrict__ r_plane) {
-  extern __shared__ float s_silu[];  // [kResidTokens][D]
-  const int tid = threadIdx.x;
-  const int t0 = blockIdx.x * kResidTokens;
-  for (int idx = tid; idx < kResidTokens * D; idx += 256) {
-    const int t = idx / D, d = idx - t * D;
-    float v = 0.f;
-    if (t0 + t < T) {
-      float u = 0.f;
-      for (int q = 0; q < KS2; ++q) u += upartial[(static_cast<long>(q) * T + t0 + t) * D + d];
-      v = u / (1.f + expf(-u));
+  constexpr int TPT = TOK / 4;           // tokens per thread
+  extern __shared__ float4 s_lds4[];
+  float* s_silu = reinterpret_cast<float*>(s_lds4);   // [TOK][D]
+  float* s_w2 = s_silu + TOK * D;                     // [256][kResidStride]
+  const int tid = threadIdx.x, lane = tid & 63, tg = tid >> 6;
+  const int t0 = blockIdx.x * TOK;
+  // u = sum of the split-K partials, sixteen elements per thread at a time so that the loads of a
+  // round are all in flight together; the TOK rows of a partial are contiguous ([t0 .. t0+TOK) x D)
+  const int n_valid = min(TOK, T - t0) * D;
+  for (int base = tid; base < TOK * D; base += 256 * 16) {
+    float u[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) u[j] = 0.f;
+    for (int q = 0; q < KS2; ++q) {
+      const float* src = upartial + (static_cast<long>(q) * T + t0) * D;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int idx = base + 256 * j;
+        if (idx < n_valid) u[j] += src[idx];
+      }
     }
-    s_silu[idx] = v;
-  }
-  __syncthreads();
-  if (tid >= E) return;
-  float acc[kResidTokens];
 #pragma unroll
-  for (int t = 0; t < kResidTokens; ++t) acc[t] = 0.f;
-  const float4* wrow = reinterpret_cast<const float4*>(w2_hat + static_cast<long>(tid) * D);
-  for (int d4 = 0; d4 < D / 4; ++d4) {
-    const float4 w = wrow[d4];
-#pragma unroll
-    for (int t = 0; t < kResidTokens; ++t) {
-      const float4 sv = *reinterpret_cast<const float4*>(s_silu + t * D + 4 * d4);
-      acc[t] = fmaf(w.x, sv.x, acc[t]);
-      acc[t] = fmaf(w.y, sv.y, acc[t]);
-      acc[t] = fmaf(w.z, sv.z, acc[t]);
-      acc[t] = fmaf(w.w, sv.w, acc[t]);
+    for (int j = 0; j < 16; ++j) {
+      const int idx = base + 256 * j;
+      if (idx < TOK * D) s_silu[idx] = (idx < n_valid) ? u[j] / (1.f + expf(-u[j])) : 0.f;
     }
   }
+  float acc[4][TPT];
 #pragma unroll
-  for (int t = 0; t < kResidTokens; ++t)
-    if (t0 + t < T) r_plane[static_cast<long>(t0 + t) * E + tid] = acc[t];
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int t = 0; t < TPT; ++t) acc[i][t] = 0.f;
+  const float* srow = s_silu + tg * TPT * D;
+  // slice of w2_hat: 256 rows x 16 columns; thread i holds float4 number i % 4 of rows i / 4, i / 4 + 64, ...
+  // (D % 8 == 0, so a float4 is inside the row or entirely past it).  The next slice is fetched into
+  // registers while the current one is consumed from LDS.
+  float4 wreg[4];
+  auto fetch = [&](int d0) {
+#pragma unroll
+    for (int pass = 0; pass < 4; ++pass) {
+      const int e = pass * 64 + (tid >> 2), c = (tid & 3) * 4;
+      wreg[pass] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (e < E && d0 + c < D) wreg[pass] = *reinterpret_cast<const float4*>(w2_hat + static_cast<long>(e) * D + d0 + c);
+    }
+  };
+  fetch(0);
+  for (int d0 = 0; d0 < D; d0 += kResidSlice) {
+    __syncthreads();  // s_silu is complete / the previous slice has been consumed
+#pragma unroll
+    for (int pass = 0; pass < 4; ++pass)
+      *reinterpret_cast<float4*>(s_w2 + (pass * 64 + (tid >> 2)) * kResidStride + (tid & 3) * 4) = wreg[pass];
+    __syncthreads();
+    if (d0 + kResidSlice < D) fetch(d0 + kResidSlice);
+#pragma unroll
+    for (int c4 = 0; c4 < kResidSlice / 4; ++c4) {
+      if (d0 + 4 * c4 < D) {
+        float4 sv[TPT], wv[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) wv[i] = *reinterpret_cast<const float4*>(s_w2 + (lane + 64 * i) * kResidStride + 4 * c4);
+#pragma unroll
+        for (int t = 0; t < TPT; ++t) sv[t] = *reinterpret_cast<const float4*>(srow + t * D + d0 + 4 * c4);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int t = 0; t < TPT; ++t) {
+            acc[i][t] = fmaf(wv[i].x, sv[t].x, acc[i][t]);
+            acc[i][t] = fmaf(wv[i].y, sv[t].y, acc[i][t]);
+            acc[i][t] = fmaf(wv[i].z, sv[t].z, acc[i][t]);
+            acc[i][t] = fmaf(wv[i].w, sv[t].w, acc[i][t]);
+          }
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int e = lane + 64 * i;
+#pragma unroll
+    for (int t = 0; t < TPT; ++t) {
+      const int tok = t0 + tg * TPT + t;
+      if (e < E && tok < T) r_plane[static_cast<long>(tok) * E + e] = acc[i][t];
+    }
+  }
 }
 
 struct RouteShape {
@@ -619,9 +672,19 @@ static int route_impl(const char* name, const void* x_bf16, const float* w_gate,
     if (resid) {
       // u = W1_hat h (one bf16 plane), then r = W2_hat silu(u) as one more plane of the logits
       launch_gate_gemm<1>(L.resid, st, x, static_cast<const bf16_t*>(w1_hat), T, H, D, upartial);
-      hipLaunchKernelGGL(predictor_residual_kernel, dim3((T + kResidTokens - 1) / kResidTokens), dim3(256),
-                         kResidTokens * D * sizeof(float), st, upartial, L.resid.ks, w2_hat, T, D, E,
-                         partial + static_cast<size_t>(sh.ks) * T * E);
+      float* r_plane = partial + static_cast<size_t>(sh.ks) * T * E;
+#define PROBE_RESID_LAUNCH(TOK)                                                                             \
+  hipLaunchKernelGGL(predictor_residual_kernel<TOK>, dim3((T + TOK - 1) / TOK), dim3(256),                  \
+                     (TOK * D + 256 * kResidStride) * sizeof(float), st, upartial, L.resid.ks, w2_hat,       \
+                     T, D, E, r_plane)
+      if (D <= 256 && T >= 32 * 512) {  // enough tokens for two workgroups per CU at 32 tokens each
+        PROBE_RESID_LAUNCH(32);
+      } else if (D <= 512) {
+        PROBE_RESID_LAUNCH(16);
+      } else {
+        PROBE_RESID_LAUNCH(8);
+      }
+#undef PROBE_RESID_LAUNCH
       planes_to_sum = sh.ks + 1;
     }
     int grid = (T + 31) / 32;
