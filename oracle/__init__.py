@@ -1,10 +1,10 @@
-"""ctypes front end of the CPU oracle (``probe_oracle.c``).
+"""ctypes front end of the CPU oracle (``probe_oracle.c``, ``planner_oracle.c``).
 
 TEST INFRASTRUCTURE ONLY: the tests, ``__graft_entry__.smoke()`` and the ``cpu_baseline``
 leg of ``bench.py`` may import this package; the product path never does.  It imports
 nothing from the HIP package and shares no code with it.
 
-The C file is compiled with gcc on first use (``build()``), into ``oracle/libprobe_oracle.so``.
+The C files are compiled with gcc on first use (``build()``), into ``oracle/libprobe_oracle.so``.
 All arrays are numpy; bf16 tensors travel as ``uint16`` bit patterns.
 """
 from __future__ import annotations
@@ -17,7 +17,7 @@ import threading
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "probe_oracle.c")
+_SRCS = [os.path.join(_HERE, "probe_oracle.c"), os.path.join(_HERE, "planner_oracle.c")]
 _LIB = os.path.join(_HERE, "libprobe_oracle.so")
 _lock = threading.Lock()
 _lib = None
@@ -25,10 +25,10 @@ _lib = None
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (plain C99 + OpenMP).  Returns the library path."""
-    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < max(os.path.getmtime(f) for f in _SRCS)
     if force or stale:
         tmp = _LIB + ".tmp%d" % os.getpid()
-        cmd = ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-o", tmp, _SRC, "-lm"]
+        cmd = ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-o", tmp] + _SRCS + ["-lm"]
         subprocess.run(cmd, check=True)
         os.replace(tmp, _LIB)
     return _LIB
@@ -231,3 +231,51 @@ def moe_layer(x_bits, w_gate, bias, tokens_per_group, k, renormalize, plan, w13_
     y = grouped_ffn(p["xp"], p["slot_offsets"], w13_list, w2_list)
     out = combine(y, p["pair_row"], r["w"])
     return dict(route=r, permute=p, y=y, out=out)
+
+
+# ------------------------------------------------------------------------------ planner
+
+def plan_greedy(n_hat, E_loc, max_replicas=3, budget=3, k_max=16, eps=0, n0=0, g_num=0, g_den=1):
+    """Algorithm 1 (greedy balance-optimal planning) on predicted tokens n_hat [R,E] (source rank, expert).
+
+    Returns dict(n [R,E,R] tokens by (origin, expert, processing rank), delta_in [R,max_replicas],
+    delta_out [R,budget], moves [k_max,3] rows (expert, r_src, r_dst), L_before, L_after, max_load,
+    n_moves)."""
+    n_hat = _chk(n_hat, np.int32)
+    R, E = n_hat.shape
+    n = np.zeros((R, E, R), np.int32)
+    delta_in = np.full((R, max(max_replicas, 1)), -1, np.int32)[:, :max_replicas]
+    delta_in = np.ascontiguousarray(delta_in)
+    delta_out = np.ascontiguousarray(np.full((R, max(budget, 1)), -1, np.int32)[:, :budget])
+    moves = np.ascontiguousarray(np.full((max(k_max, 1), 3), -1, np.int32)[:k_max])
+    stats = np.zeros((4,), np.int64)
+    i64 = C.c_int64
+    rc = _load().oracle_plan_greedy(_p(n_hat, C.c_int32), R, E, int(E_loc), int(max_replicas), int(budget),
+                                    int(k_max), i64(int(eps)), i64(int(n0)), i64(int(g_num)), i64(int(g_den)),
+                                    _p(n, C.c_int32), _p(delta_in, C.c_int32), _p(delta_out, C.c_int32),
+                                    _p(moves, C.c_int32), _p(stats, C.c_int64))
+    if rc != 0:
+        raise ValueError("oracle plan_greedy failed: %d" % rc)
+    return dict(n=n, delta_in=delta_in, delta_out=delta_out, moves=moves, L_before=int(stats[0]),
+                L_after=int(stats[1]), max_load=int(stats[2]), n_moves=int(stats[3]))
+
+
+def plan_for_rank(n, delta_in, E_loc, rank):
+    """The plan of plan_greedy in the layout probe_permute consumes, as seen from one rank."""
+    n = _chk(n, np.int32)
+    R, E, _ = n.shape
+    delta_in = _chk(delta_in, np.int32)
+    max_replicas = delta_in.shape[1]
+    rep_off = np.zeros((E + 1,), np.int32)
+    cap = E + R * max_replicas
+    rep_slot = np.full((cap,), -1, np.int32)
+    rep_weight = np.zeros((cap,), np.int32)
+    slot_expert = np.full((E_loc + max_replicas,), -1, np.int32)
+    rc = _load().oracle_plan_for_rank(_p(n, C.c_int32), _p(delta_in, C.c_int32), R, E, int(E_loc), max_replicas,
+                                      int(rank), _p(rep_off, C.c_int32), _p(rep_slot, C.c_int32),
+                                      _p(rep_weight, C.c_int32), _p(slot_expert, C.c_int32))
+    if rc != 0:
+        raise ValueError("oracle plan_for_rank failed: %d" % rc)
+    used = int(rep_off[E])
+    return dict(rep_off=rep_off, rep_slot=rep_slot[:used].copy(), rep_weight=rep_weight[:used].copy(),
+                num_slots=E_loc + max_replicas, slot_expert=slot_expert)
