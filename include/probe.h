@@ -9,6 +9,7 @@
  *   probe_route_topk    router of layer L: logits W_L h + b_L, softmax, k largest
  *   probe_predict_topk  gate-initialised lookahead predictor (Eq. 7, frozen prior term);
  *                       probe_predict_topk_residual adds the trainable residual MLP of Eq. 7
+ *   probe_plan_greedy   the greedy planner of Sec. 4.3 (Algorithm 1): predicted workload -> plan
  *   probe_permute       group (token, top-k position) pairs by the expert replica that the
  *                       balance plan (placement P, assignment A; Sec. 3.1, Sec. 4.3) gives them
  *   probe_grouped_ffn   grouped SwiGLU expert FFN over native + replicated experts
@@ -208,6 +209,57 @@ int probe_grouped_ffn(const void* xp_bf16, const int32_t* slot_offsets,
  */
 int probe_combine(const void* y_bf16, const int32_t* pair_row, const float* topk_w, int T,
                   int H, int k, void* out_bf16, void* stream);
+
+/* ---------------------------------------------------------------------------- planner ---
+ *
+ * Greedy balance-optimal planning (Sec. 4.3, Algorithm 1) on the device: from the all-gathered
+ * prediction to the plan probe_permute consumes, without a host round trip.
+ *
+ * Baseline placement P': expert e lives on rank e / E_loc.  The loop repeatedly takes the rank with
+ * the largest latency L_r (bottleneck) and the valid rank with the smallest (helper), copies the
+ * bottleneck's heaviest movable expert to the helper if both transfer budgets allow it, lets the
+ * helper's own tokens of that expert stay at home (locality first) and redirects tokens whose origin
+ * holds no copy from the bottleneck to the helper until the bottleneck's token load is down to the
+ * cluster average (water-filling).  A move is kept when it lowers max_r L_r by more than eps; at most
+ * k_max moves.  The paper names the terms of L_r but not their constants; here
+ *     L_r = g_den * sum_{e: n_{e,r} > 0} (n_{e,r} + n0) + 2 * g_num * max(V_in_r, V_out_r)
+ * (eta_g(n) = n / (n + n0) of Sec. 3.2; V_in / V_out = tokens received from / sent to other ranks,
+ * Sec. 3.3, no deduplication).  All arithmetic is integer; ties go to the lower rank / expert id.
+ */
+typedef struct {
+  int32_t max_replicas; /* replica slots per rank, |Delta^in_r| <= min(max_replicas, budget); <= 8 */
+  int32_t budget;       /* experts a rank may send and may receive inside the hiding window; <= 8   */
+  int32_t k_max;        /* accepted moves at most (Sec. 5 uses 16); <= 64                             */
+  int64_t eps;          /* a move must lower the bottleneck latency by more than this                */
+  int64_t n0;           /* tokens at which a grouped GEMM reaches half of its peak rate              */
+  int64_t g_num, g_den; /* network time per token / compute time per token, g_den >= 1               */
+} probe_planner_params;
+
+/*
+ *   n_hat        device, int32 [R,E]  tokens that originate on rank rs and are predicted for expert e
+ *                (negative entries are read as 0)
+ *   rank         the rank whose view of the plan is written to rep_off / rep_slot / rep_weight
+ *   params       host pointer
+ *   rep_off      device, int32 [E+1]                    (out)  } the probe_plan arrays: one replica per
+ *   rep_slot     device, int32 [E + R*max_replicas]     (out)  } rank that holds the expert, ascending
+ *   rep_weight   device, int32 [E + R*max_replicas]     (out)  } rank; weight = tokens planned for it
+ *                (an expert with no predicted token keeps weight 1 on its home copy); local slots:
+ *                native experts 0..E_loc-1, then replicas in the order they were added
+ *   slot_expert  device, int32 [E_loc + max_replicas]   (out)  expert each local slot must hold, -1 = none
+ *   delta_in     device, int32 [R,max_replicas]         (out)  experts copied onto each rank, -1 padded
+ *   delta_out    device, int32 [R,budget] or NULL       (out)  experts each rank sends, -1 padded
+ *   moves        device, int32 [k_max,3]                (out)  (expert, r_src, r_dst) per accepted move
+ *   stats        device, int64 [4]  (out)  max L before, max L after, max token load after, moves
+ *   n_assign     device, int32 [R,E,R] or NULL          (out)  tokens by (origin, expert, processing rank)
+ * Limits: R <= 16, E <= 256, E_loc * R >= E.  One workgroup; meant to run beside the main track.
+ */
+size_t probe_plan_greedy_workspace_bytes(int R, int E);
+
+int probe_plan_greedy(const int32_t* n_hat, int R, int E, int E_loc, int rank,
+                      const probe_planner_params* params, int32_t* rep_off, int32_t* rep_slot,
+                      int32_t* rep_weight, int32_t* slot_expert, int32_t* delta_in, int32_t* delta_out,
+                      int32_t* moves, int64_t* stats, int32_t* n_assign, void* workspace,
+                      size_t workspace_bytes, void* stream);
 
 /* -------------------------------------------------------------------- measurement aid ---
  *

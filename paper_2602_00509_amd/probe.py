@@ -28,6 +28,11 @@ class ProbeError(RuntimeError):
         self.code = code
 
 
+class _PlannerParams(C.Structure):
+    _fields_ = [("max_replicas", C.c_int32), ("budget", C.c_int32), ("k_max", C.c_int32), ("eps", C.c_int64),
+                ("n0", C.c_int64), ("g_num", C.c_int64), ("g_den", C.c_int64)]
+
+
 class _Plan(C.Structure):
     _fields_ = [("rep_off", C.c_void_p), ("rep_slot", C.c_void_p), ("rep_weight", C.c_void_p),
                 ("num_slots", C.c_int32)]
@@ -64,6 +69,11 @@ def lib():
         L.probe_grouped_ffn.argtypes = ([C.c_void_p] * 4 + [C.c_int] * 4 + [C.c_void_p] * 2 +
                                         [C.c_size_t, C.c_void_p])
         L.probe_combine.argtypes = [C.c_void_p] * 3 + [C.c_int] * 3 + [C.c_void_p] * 2
+        L.probe_plan_greedy_workspace_bytes.restype = C.c_size_t
+        L.probe_plan_greedy_workspace_bytes.argtypes = [C.c_int, C.c_int]
+        L.probe_plan_greedy.restype = C.c_int
+        L.probe_plan_greedy.argtypes = ([C.c_void_p] + [C.c_int] * 4 + [C.POINTER(_PlannerParams)] +
+                                        [C.c_void_p] * 10 + [C.c_size_t, C.c_void_p])
         L.probe_peak_mfma_flops_per_launch.restype = C.c_double
         L.probe_peak_mfma_flops_per_launch.argtypes = [C.c_int, C.c_int]
         L.probe_peak_mfma.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
@@ -180,6 +190,37 @@ def predict_topk_residual(h_prev, w_gate_next, bias_next, tokens_per_group, w1_h
     """probe_predict_topk_residual: Eq. 7 in full; w1_hat bf16 [D,H], w2_hat fp32 [E,D]."""
     return _route(lib().probe_predict_topk_residual, h_prev, w_gate_next, bias_next, tokens_per_group, k,
                   renormalize, want_probs, want_counts, out, workspace, stream, residual=(w1_hat, w2_hat))
+
+
+# ------------------------------------------------------------------------------ planner
+
+def plan_greedy(n_hat, E_loc, rank=0, max_replicas=3, budget=3, k_max=16, eps=0, n0=0, g_num=0, g_den=1, *,
+                want_assignment=False, workspace=None, stream=None):
+    """probe_plan_greedy: Algorithm 1 on n_hat int32 [R,E]; every output stays on the device.
+
+    Returns dict(plan=Plan usable by permute, rep_off, rep_slot, rep_weight, slot_expert, delta_in,
+    delta_out, moves, stats int64 [4], n (optional))."""
+    R, E = n_hat.shape
+    _want(n_hat, torch.int32, (R, E), "n_hat")
+    dev = n_hat.device
+    i32 = dict(dtype=torch.int32, device=dev)
+    out = dict(rep_off=torch.empty((E + 1,), **i32), rep_slot=torch.empty((E + R * max_replicas,), **i32),
+               rep_weight=torch.empty((E + R * max_replicas,), **i32),
+               slot_expert=torch.empty((E_loc + max_replicas,), **i32),
+               delta_in=torch.empty((R, max_replicas), **i32), delta_out=torch.empty((R, budget), **i32),
+               moves=torch.empty((k_max, 3), **i32), stats=torch.empty((4,), dtype=torch.int64, device=dev))
+    if want_assignment:
+        out["n"] = torch.empty((R, E, R), **i32)
+    params = _PlannerParams(max_replicas, budget, k_max, eps, n0, g_num, g_den)
+    workspace = _ws(workspace, int(lib().probe_plan_greedy_workspace_bytes(R, E)), dev)
+    rc = lib().probe_plan_greedy(_ptr(n_hat), R, E, E_loc, rank, C.byref(params), _ptr(out["rep_off"]),
+                                 _ptr(out["rep_slot"]), _ptr(out["rep_weight"]), _ptr(out["slot_expert"]),
+                                 _ptr(out["delta_in"]), _ptr(out["delta_out"]), _ptr(out["moves"]),
+                                 _ptr(out["stats"]), _ptr(out.get("n")), _ptr(workspace), workspace.numel(),
+                                 _stream(stream))
+    _check(rc)
+    out["plan"] = Plan(out["rep_off"], out["rep_slot"], out["rep_weight"], E_loc + max_replicas, dev)
+    return out
 
 
 # ------------------------------------------------------------------------------ permute

@@ -1,0 +1,119 @@
+"""GPU parity of probe_plan_greedy (Algorithm 1 as one workgroup) against the sequential oracle: every
+integer output bit-exact, and the device-resident loop predict -> plan -> permute."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2602_00509_amd import workload as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def probe():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    from paper_2602_00509_amd import probe as p
+    p.lib()
+    return p
+
+
+@pytest.fixture(scope="module")
+def G():
+    import gpu_util
+    return gpu_util
+
+
+def _random_nhat(seed, R, E, scale=200, zipf=1.2):
+    rng = np.random.default_rng(seed)
+    pop = (np.arange(1, E + 1) ** -zipf)[rng.permutation(E)]
+    lam = scale * pop / pop.mean()
+    return rng.poisson(lam, size=(R, E)).astype(np.int32)
+
+
+def _compare(probe, oracle, nh, E_loc, ranks, **kw):
+    R, E = nh.shape
+    o = oracle.plan_greedy(nh, E_loc, **kw)
+    d_nh = torch.from_numpy(nh).cuda()
+    for rank in ranks:
+        g = probe.plan_greedy(d_nh, E_loc, rank=rank, want_assignment=True, **kw)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(g["moves"].cpu().numpy(), o["moves"])
+        np.testing.assert_array_equal(g["delta_in"].cpu().numpy(), o["delta_in"])
+        np.testing.assert_array_equal(g["delta_out"].cpu().numpy(), o["delta_out"])
+        np.testing.assert_array_equal(g["n"].cpu().numpy(), o["n"])
+        assert g["stats"].cpu().tolist() == [o["L_before"], o["L_after"], o["max_load"], o["n_moves"]]
+        p = oracle.plan_for_rank(o["n"], o["delta_in"], E_loc, rank)
+        used = int(p["rep_off"][E])
+        np.testing.assert_array_equal(g["rep_off"].cpu().numpy(), p["rep_off"])
+        np.testing.assert_array_equal(g["rep_slot"].cpu().numpy()[:used], p["rep_slot"])
+        np.testing.assert_array_equal(g["rep_weight"].cpu().numpy()[:used], p["rep_weight"])
+        np.testing.assert_array_equal(g["slot_expert"].cpu().numpy(), p["slot_expert"])
+    return o
+
+
+@pytest.mark.parametrize("seed,R,E,E_loc", [(1, 4, 16, 4), (2, 8, 64, 8), (3, 8, 256, 32), (4, 3, 10, 4),
+                                            (5, 16, 128, 8), (6, 16, 256, 16), (7, 1, 8, 8), (8, 2, 3, 2)])
+@pytest.mark.parametrize("cost", [dict(n0=0, g_num=0, g_den=1), dict(n0=64, g_num=1, g_den=4),
+                                  dict(n0=16, g_num=3, g_den=2, eps=40)])
+def test_planner_matches_oracle_bit_for_bit(oracle, probe, seed, R, E, E_loc, cost):
+    print("case planner R=%d E=%d" % (R, E), flush=True)
+    nh = _random_nhat(seed, R, E)
+    o = _compare(probe, oracle, nh, E_loc, ranks=sorted({0, R // 2, R - 1}), max_replicas=3, budget=2, k_max=16, **cost)
+    if R >= 4 and cost.get("eps", 0) == 0:
+        assert o["n_moves"] >= 2          # the cases exercise the loop, not only its exit
+
+
+def test_planner_hand_worked_example_and_limits(oracle, probe):
+    """The three-rank example worked out by hand in the oracle's pins, then the exits of the loop."""
+    nh = np.array([[20, 0, 0], [30, 10, 0], [40, 0, 10]], np.int32)
+    g = probe.plan_greedy(torch.from_numpy(nh).cuda(), 1, rank=1, max_replicas=2, budget=2, k_max=16)
+    torch.cuda.synchronize()
+    assert g["stats"].cpu().tolist() == [90, 50, 50, 2]
+    assert g["moves"].cpu().numpy()[:2].tolist() == [[0, 0, 1], [0, 1, 2]]
+    assert g["rep_weight"].cpu().numpy()[:5].tolist() == [20, 30, 40, 10, 10]
+    assert g["rep_slot"].cpu().numpy()[:5].tolist() == [-1, 1, -1, 0, -1]
+    big = _random_nhat(11, 8, 64)
+    for kw in (dict(max_replicas=3, budget=0, k_max=16), dict(max_replicas=0, budget=3, k_max=16),
+               dict(max_replicas=3, budget=3, k_max=0), dict(max_replicas=8, budget=8, k_max=64),
+               dict(max_replicas=1, budget=3, k_max=16, n0=32, g_num=1, g_den=1)):
+        _compare(probe, oracle, big, 8, ranks=[0, 5], **kw)
+    # all-zero prediction: nothing to plan, every expert keeps a unit weight at home
+    z = np.zeros((4, 16), np.int32)
+    o = _compare(probe, oracle, z, 4, ranks=[2], max_replicas=2, budget=2, k_max=16)
+    assert o["n_moves"] == 0
+
+
+def test_predict_plan_permute_stays_on_the_device(oracle, probe, G):
+    """Predicted top-k of 8 virtual source ranks -> n_hat -> plan on the device -> permute of the real routing
+    with that plan; the permutation is checked against the oracle fed with the oracle's plan."""
+    cfg = wl.small_config(T=2048, H=128, E=64, k=4, F=128, E_loc=8, n_rep=0, zipf_s=1.3, ep=8, cid=94)
+    R, E, E_loc, k, T = 8, cfg.E, 8, cfg.k, cfg.T
+    L = G.Layer(cfg, 0)
+    pred = probe.predict_topk(L.d_x, L.d_wg, L.d_bias, L.tpg, k, True)
+    # tokens are dealt to source ranks in contiguous chunks of T / R (test plumbing, not part of the path)
+    chunk = T // R
+    onehot = torch.zeros((R, E), dtype=torch.int32, device="cuda")
+    src = (torch.arange(T, device="cuda") // chunk).clamp(max=R - 1).repeat_interleave(k)
+    onehot.index_put_((src, pred["idx"].reshape(-1).long()), torch.ones(T * k, dtype=torch.int32, device="cuda"),
+                      accumulate=True)
+    kw = dict(max_replicas=3, budget=3, k_max=16, n0=16, g_num=1, g_den=2)
+    g = probe.plan_greedy(onehot, E_loc, rank=0, **kw)
+    route = probe.route_topk(L.d_x, L.d_wg, L.d_bias, L.tpg, k, True)
+    perm = probe.permute(route["idx"], g["plan"], L.d_x)
+    torch.cuda.synchronize()
+    nh = onehot.cpu().numpy()
+    np.testing.assert_array_equal(nh.sum(0), pred["counts"].cpu().numpy())
+    o = oracle.plan_greedy(nh, E_loc, **kw)
+    assert o["n_moves"] >= 1 and g["stats"].cpu().tolist()[3] == o["n_moves"]
+    p = oracle.plan_for_rank(o["n"], o["delta_in"], E_loc, 0)
+    o_p = oracle.permute(route["idx"].cpu().numpy(), p["rep_off"], p["rep_slot"], p["rep_weight"], p["num_slots"], L.x)
+    np.testing.assert_array_equal(perm["pair_row"].cpu().numpy(), o_p["pair_row"])
+    np.testing.assert_array_equal(perm["slot_counts"].cpu().numpy(), o_p["slot_counts"])
+    nl = o_p["n_local"]
+    np.testing.assert_array_equal(G.bits_of(perm["xp"][:nl]), o_p["xp"][:nl])
+    # rank 0's replica slots received rows exactly when the plan gave them a positive share
+    se = g["slot_expert"].cpu().numpy()
+    for s in range(E_loc, E_loc + 3):
+        if se[s] >= 0:
+            assert o_p["slot_counts"][s] > 0
