@@ -116,10 +116,11 @@ def main():
     out = torch.empty((T, H), dtype=torch.bfloat16, device=dev)
 
     # plans: the host recipe of the workload, from each batch's routed counts (set-up, untimed)
-    plans, d_plans, n_locals, slot_experts, active_slots = [], [], [], [], []
+    plans, d_plans, n_locals, slot_experts, active_slots, all_counts = [], [], [], [], [], []
     for b in range(nb):
         probe.route_topk(d_xs[b], d_wg, d_bias[b], tpg, k, True, out=r_out, workspace=ws_route)
         counts = r_out["counts"].cpu().numpy()
+        all_counts.append(counts.copy())
         plan = wl.build_plan(cfg, counts)
         plans.append(plan)
         d_plans.append(probe.Plan(plan["rep_off"], plan["rep_slot"], plan["rep_weight"], plan["num_slots"], dev))
@@ -226,6 +227,27 @@ def main():
     result["roofline"]["peak_measured"] = measure_peaks(torch, probe, dev)
     result["roofline"]["frac_of_measured_mfma_random"] = (
         ffn_tflops / result["roofline"]["peak_measured"]["mfma_only_random_operands_tflops"])
+
+    # the greedy planner (Algorithm 1) on the device, timed on its own: the batches stand in for the source
+    # ranks whose predicted counts an all-gather would deliver; not part of `value`
+    ep = cfg.E // cfg.E_loc
+    if 2 <= ep <= 16 and cfg.E_loc * ep == E:
+        rows = [all_counts[r % nb] for r in range(ep)]
+        d_nhat = torch.from_numpy(np.stack(rows).astype(np.int32)).to(dev)
+        kw = dict(max_replicas=cfg.n_rep if cfg.n_rep else 3, budget=3, k_max=16, n0=64, g_num=1, g_den=4)
+        for _ in range(3):
+            pl = probe.plan_greedy(d_nhat, cfg.E_loc, rank=0, **kw)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            pl = probe.plan_greedy(d_nhat, cfg.E_loc, rank=0, **kw)
+        e1.record()
+        torch.cuda.synchronize()
+        st = pl["stats"].cpu().tolist()
+        result["planner"] = {"us_per_call": e0.elapsed_time(e1) * 1e3 / 20, "ranks": ep, "experts": E,
+                             "params": kw, "moves": st[3], "bottleneck_latency_before": st[0],
+                             "bottleneck_latency_after": st[1]}
 
     if args.calibrate_copy:
         src = torch.ones((1 << 28,), dtype=torch.float32, device=dev)      # 1 GiB
