@@ -14,6 +14,7 @@
 //               experts with wave ballots, computes slot and row analytically -> pair_row, row_pair
 //   4. scatter  one thread per 16-byte chunk of a token row: read x once, write it to each of
 //               the token's local rows                                   -> xp
+// A batch of at most 1024 pairs (decode) runs steps 1-3 as one workgroup in one launch.
 //
 // Steps 1-3 touch only T*k integers; step 4 carries the HBM traffic (T*H*2 bytes read at
 // most, n_local*H*2 written).
@@ -275,6 +276,157 @@ __global__ __launch_bounds__(kPermWaves* kWave) void permute_index_kernel(
   }
 }
 
+// Steps 1-3 in one workgroup, for batches of at most 1024 pairs (decode): the block histogram is the
+// global one, so the scan over blocks disappears and the whole index computation is one launch.
+__global__ __launch_bounds__(kPermWaves* kWave) void permute_small_kernel(
+    const int32_t* __restrict__ topk_idx, int N, int E, const int32_t* __restrict__ rep_off,
+    const int32_t* __restrict__ rep_slot, const int32_t* __restrict__ rep_weight, int S,
+    int32_t* __restrict__ slot_counts, int32_t* __restrict__ slot_offsets, int32_t* __restrict__ n_local,
+    int32_t* __restrict__ pair_row, int32_t* __restrict__ row_pair) {
+  __shared__ int32_t cnt_mem[kPermWaves][PROBE_MAX_EXPERTS];
+  __shared__ int32_t e_lo[PROBE_MAX_EXPERTS], e_hi[PROBE_MAX_EXPERTS], e_P[PROBE_MAX_EXPERTS];
+  __shared__ int32_t s_off[PROBE_MAX_SLOTS + 1], sc[PROBE_MAX_SLOTS];
+  __shared__ int32_t s_rw[kRepLds], s_rs[kRepLds];
+  __shared__ int32_t wave_tot[kPermWaves];
+  const int tid = threadIdx.x, w = tid / kWave, lane = lane_id();
+  volatile int32_t* cnt_w = cnt_mem[w];  // volatile: keep every lane's read before the leader's update
+  const long base = static_cast<long>(w) * kSegPairs;
+  const int R = rep_off[E];
+  const bool staged = R <= kRepLds;
+  if (staged)
+    for (int i = tid; i < R; i += kPermWaves * kWave) {
+      s_rw[i] = rep_weight[i];
+      s_rs[i] = rep_slot[i];
+    }
+  const int32_t* rw = staged ? s_rw : rep_weight;
+  const int32_t* rs = staged ? s_rs : rep_slot;
+  for (int e = tid; e < E; e += kPermWaves * kWave) {
+    int lo = rep_off[e], hi = rep_off[e + 1], P = 0;
+    for (int i = lo; i < hi; ++i) P += rep_weight[i];
+    e_lo[e] = lo;
+    e_hi[e] = hi;
+    e_P[e] = P;
+  }
+  for (int s = tid; s < S; s += kPermWaves * kWave) sc[s] = 0;
+  // counts of this wave's segment
+  for (int e = lane; e < E; e += kWave) cnt_w[e] = 0;
+  int seg_e[kSegIters];
+#pragma unroll
+  for (int it = 0; it < kSegIters; ++it) {
+    long p = base + it * kWave + lane;
+    int e = p < N ? topk_idx[p] : -1;
+    seg_e[it] = e;
+    bool valid = static_cast<unsigned>(e) < static_cast<unsigned>(E);
+    uint64_t m = match_key8(e, valid);
+    if (valid && (m & lanemask_lt()) == 0) cnt_w[e] += __popcll(m);
+  }
+  __syncthreads();
+  // rows each replica receives: floor(n/P) w_i + clamp(n mod P - c_{i-1}, 0, w_i)
+  for (int e = tid; e < E; e += kPermWaves * kWave) {
+    int n_e = 0;
+#pragma unroll
+    for (int q = 0; q < kPermWaves; ++q) n_e += cnt_mem[q][e];
+    const int P = e_P[e];
+    if (P > 0) {
+      int full = n_e / P, rem = n_e - full * P, cum = 0;
+      for (int i = e_lo[e]; i < e_hi[e]; ++i) {
+        int wgt = rw[i];
+        int part_rows = min(max(rem - cum, 0), wgt);
+        int slot = rs[i];
+        if (slot >= 0 && slot < S) sc[slot] = full * wgt + part_rows;
+        cum += wgt;
+      }
+    }
+  }
+  __syncthreads();
+  // exclusive prefix sum over the slots, 4 consecutive slots per thread
+  int v[4], local = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    int s = tid * 4 + i;
+    v[i] = s < S ? sc[s] : 0;
+    local += v[i];
+  }
+  int incl = local;
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    int o = __shfl_up(incl, d, kWave);
+    if (lane >= d) incl += o;
+  }
+  if (lane == kWave - 1) wave_tot[w] = incl;
+  __syncthreads();
+  {
+    int excl = incl - local;
+    for (int i = 0; i < w; ++i) excl += wave_tot[i];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int s = tid * 4 + i;
+      if (s < S) {
+        slot_counts[s] = v[i];
+        slot_offsets[s] = excl;
+        s_off[s] = excl;
+      }
+      excl += v[i];
+    }
+    if (tid == kPermWaves * kWave - 1) {
+      slot_offsets[S] = excl;
+      n_local[0] = excl;
+      s_off[S] = excl;
+    }
+  }
+  // arrival rank at the start of this wave's segment = counts of the earlier waves
+  int start[PROBE_MAX_EXPERTS / kWave];
+#pragma unroll
+  for (int i = 0; i < PROBE_MAX_EXPERTS / kWave; ++i) {
+    int e = lane + i * kWave;
+    int a = 0;
+    if (e < E)
+      for (int q = 0; q < w; ++q) a += cnt_mem[q][e];
+    start[i] = a;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < PROBE_MAX_EXPERTS / kWave; ++i) {
+    int e = lane + i * kWave;
+    if (e < E) cnt_w[e] = start[i];
+  }
+  const int n_loc = s_off[S];
+#pragma unroll
+  for (int it = 0; it < kSegIters; ++it) {
+    long p = base + it * kWave + lane;
+    int e = seg_e[it];
+    bool valid = static_cast<unsigned>(e) < static_cast<unsigned>(E);
+    uint64_t m = match_key8(e, valid);
+    if (p < N && !valid) {  // expert id out of range: the pair is computed nowhere on this GPU
+      pair_row[p] = -1;
+      if (p >= n_loc) row_pair[p] = -1;
+    }
+    if (valid) {
+      int before = __popcll(m & lanemask_lt());
+      int j = cnt_w[e] + before;
+      int lo = e_lo[e], hi = e_hi[e], P = e_P[e];
+      int row = -1;
+      if (P > 0) {
+        int full = j / P, u = j - full * P, cum = 0;
+        for (int i = lo; i < hi; ++i) {
+          int wgt = rw[i];
+          if (u < cum + wgt) {
+            int slot = rs[i];
+            if (slot >= 0 && slot < S) row = s_off[slot] + full * wgt + (u - cum);
+            if (row >= N) row = -1;
+            break;
+          }
+          cum += wgt;
+        }
+      }
+      pair_row[p] = row;
+      if (row >= 0) row_pair[row] = static_cast<int32_t>(p);
+      if (p >= n_loc) row_pair[p] = -1;
+    }
+    if (valid && (m & lanemask_lt()) == 0) cnt_w[e] += __popcll(m);
+  }
+}
+
 // Step 4.
 template <int K>
 __global__ __launch_bounds__(256) void permute_scatter_kernel(const u32x4* __restrict__ x,
@@ -345,15 +497,22 @@ extern "C" int probe_permute(const int32_t* topk_idx, const probe_plan* plan, co
   int U = num_blocks(N);
   int32_t* seg = static_cast<int32_t*>(workspace);
   int seg_blocks = U;
-  if (U > 0)
-    hipLaunchKernelGGL(permute_hist_kernel, dim3(seg_blocks), dim3(kPermWaves * kWave), 0, st, topk_idx, N,
-                       E, seg);
-  hipLaunchKernelGGL(permute_scan_kernel, dim3(1), dim3(1024), 0, st, seg, U, E, plan->rep_off,
-                     plan->rep_slot, plan->rep_weight, S, slot_counts, slot_offsets, n_local);
-  if (U > 0) {
-    hipLaunchKernelGGL(permute_index_kernel, dim3(seg_blocks), dim3(kPermWaves * kWave), 0, st, topk_idx,
-                       N, E, seg, plan->rep_off, plan->rep_slot, plan->rep_weight, slot_offsets, S,
+  if (U == 1) {
+    hipLaunchKernelGGL(permute_small_kernel, dim3(1), dim3(kPermWaves * kWave), 0, st, topk_idx, N, E,
+                       plan->rep_off, plan->rep_slot, plan->rep_weight, S, slot_counts, slot_offsets, n_local,
                        pair_row, row_pair);
+  } else {
+    if (U > 0)
+      hipLaunchKernelGGL(permute_hist_kernel, dim3(seg_blocks), dim3(kPermWaves * kWave), 0, st, topk_idx, N,
+                         E, seg);
+    hipLaunchKernelGGL(permute_scan_kernel, dim3(1), dim3(1024), 0, st, seg, U, E, plan->rep_off,
+                       plan->rep_slot, plan->rep_weight, S, slot_counts, slot_offsets, n_local);
+    if (U > 0)
+      hipLaunchKernelGGL(permute_index_kernel, dim3(seg_blocks), dim3(kPermWaves * kWave), 0, st, topk_idx,
+                         N, E, seg, plan->rep_off, plan->rep_slot, plan->rep_weight, slot_offsets, S,
+                         pair_row, row_pair);
+  }
+  if (U > 0) {
     int cpr = H / 8;
     long total = static_cast<long>(T) * cpr;
     unsigned grid = static_cast<unsigned>((total + 255) / 256);

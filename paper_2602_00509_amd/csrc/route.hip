@@ -562,6 +562,8 @@ struct RouteShape {
   size_t planes_bytes, partial_bytes;
 };
 
+constexpr int kMaxSplitK = 16;
+
 static RouteShape route_shape(int T, int H, int E) {
   RouteShape s;
   // 256-token tiles when a split of 8 or less still gives every CU a workgroup; they aim at one
@@ -575,6 +577,7 @@ static RouteShape route_shape(int T, int H, int E) {
   const int target = s.bm == 256 ? 256 : 512;
   int want = tiles > 0 ? (target + tiles - 1) / tiles : 1;
   if (want < 1) want = 1;
+  if (want > kMaxSplitK) want = kMaxSplitK;  // the softmax kernel adds the slices one after another
   if (want > ksteps) want = ksteps;
   int steps_per = (ksteps + want - 1) / want;
   s.k_chunk = steps_per * GBK;
