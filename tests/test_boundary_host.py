@@ -78,6 +78,22 @@ def test_bad_arguments_are_rejected_without_a_launch(L):
     assert pr(fake, fake, None, 1, 1, fake, fake, 16, 16, 64, 8, 2, 1, fake, fake, None, None, fake,
               C.c_size_t(L.probe_route_topk_workspace_bytes(16, 64, 8, 2)), None) == -4   # needs more than the router
     assert L.probe_predict_topk_residual_workspace_bytes(16, 64, 8, 2, 16) > L.probe_route_topk_workspace_bytes(16, 64, 8, 2)
+    # planner
+    from paper_2602_00509_amd.probe import _PlannerParams
+    pp = _PlannerParams(3, 3, 16, 0, 0, 0, 1)
+    pg = lambda R, E, El, rank, par, ws=big, nh=fake: L.probe_plan_greedy(
+        nh, R, E, El, rank, C.byref(par) if par else None, fake, fake, fake, fake, fake, fake, fake, fake, None, fake, ws, None)
+    assert pg(8, 64, 8, 0, None) == -1                                   # params NULL
+    assert pg(8, 64, 4, 0, pp) == -1                                     # E_loc * R < E
+    assert pg(8, 64, 8, 8, pp) == -1                                     # rank out of range
+    assert pg(8, 64, 8, 0, _PlannerParams(3, 3, 16, 0, 0, 0, 0)) == -1   # g_den < 1
+    assert pg(32, 64, 2, 0, pp) == -2                                    # R > 16
+    assert pg(8, 512, 64, 0, pp) == -2                                   # E > 256
+    assert pg(8, 64, 8, 0, _PlannerParams(9, 3, 16, 0, 0, 0, 1)) == -2   # max_replicas > 8
+    assert pg(8, 64, 8, 0, _PlannerParams(3, 3, 65, 0, 0, 0, 1)) == -2   # k_max > 64
+    assert pg(8, 64, 8, 0, pp, nh=None) == -1
+    assert pg(8, 64, 8, 0, pp, ws=C.c_size_t(64)) == -4 and "workspace" in err()
+    assert L.probe_plan_greedy_workspace_bytes(8, 64) >= 64 * 8 * 8 * 4
     # permute
     plan = _Plan(0x1000, 0x1000, 0x1000, 4)
     args = lambda **kw: None
