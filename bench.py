@@ -46,6 +46,9 @@ def main():
     ap.add_argument("--residual-width", type=int, default=0,
                     help="width D of the predictor's residual MLP (Eq. 7); 0 = residual at its zero initialisation, "
                          "i.e. probe_predict_topk")
+    ap.add_argument("--fused-route-predict", action="store_true",
+                    help="one probe_route_predict_topk call instead of predict_topk + route_topk (the predictor of "
+                         "the next layer reads the same hidden states as this layer's router)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -98,6 +101,8 @@ def main():
                       w=torch.empty((T, k), dtype=torch.float32, device=dev),
                       counts=torch.empty((E,), dtype=torch.int32, device=dev))
     ws_route = torch.empty(probe.route_topk_workspace_bytes(T, H, E, k), dtype=torch.uint8, device=dev)
+    ws_fused = (torch.empty(probe.route_predict_topk_workspace_bytes(T, H, E, k), dtype=torch.uint8, device=dev)
+                if args.fused_route_predict else None)
     D = args.residual_width
     if D:
         rng = np.random.default_rng(1000 + cfg.cid)
@@ -140,13 +145,18 @@ def main():
             if ev is not None:
                 ev[i].record()
         mark(0)
-        if D:
+        if args.fused_route_predict:
+            probe.route_predict_topk(d_xs[b], d_wg, d_bias[b], d_wg_next, d_bias_next[b], tpg, k, True, out=r_out,
+                                     pred_out=p_out_pred, workspace=ws_fused)
+            mark(1)
+        elif D:
             probe.predict_topk_residual(d_xs[b], d_wg_next, d_bias_next[b], tpg, d_w1, d_w2, k, True, out=p_out_pred,
                                         workspace=ws_pred)
         else:
             probe.predict_topk(d_xs[b], d_wg_next, d_bias_next[b], tpg, k, True, out=p_out_pred, workspace=ws_route)
-        mark(1)
-        probe.route_topk(d_xs[b], d_wg, d_bias[b], tpg, k, True, out=r_out, workspace=ws_route)
+        if not args.fused_route_predict:
+            mark(1)
+            probe.route_topk(d_xs[b], d_wg, d_bias[b], tpg, k, True, out=r_out, workspace=ws_route)
         mark(2)
         probe.permute(r_out["idx"], d_plans[b], d_xs[b], out=perm_out, workspace=ws_perm)
         mark(3)
@@ -203,8 +213,10 @@ def main():
         "config": {"workload": "cfg%d %s: T=%d H=%d E=%d top-%d F=%d, %d native + %d replica slots, Zipf s=%.1f, "
                                "%d rotating batches" % (cfg.cid, cfg.name, T, H, E, k, F, cfg.E_loc, cfg.n_rep,
                                                         cfg.zipf_s, nb),
-                   "step": ("predict_topk_residual(D=%d)" % D if D else "predict_topk") +
-                           " + route_topk + permute + grouped_ffn + combine",
+                   "step": ("route_predict_topk (stage time reported under predict, route = 0)"
+                            if args.fused_route_predict else
+                            ("predict_topk_residual(D=%d)" % D if D else "predict_topk") + " + route_topk") +
+                           " + permute + grouped_ffn + combine",
                    "rows_per_step_mean": nl_mean, "active_slots_mean": act_mean},
         "stage_ms": mean_ms,
         "stage_ms_min": {n: float(np.min(v)) for n, v in stage_ms.items()},

@@ -210,6 +210,23 @@ int probe_grouped_ffn(const void* xp_bf16, const int32_t* slot_offsets,
 int probe_combine(const void* y_bf16, const int32_t* pair_row, const float* topk_w, int T,
                   int H, int k, void* out_bf16, void* stream);
 
+/* Router of layer L-1 and predictor of layer L (residual at its zero initialisation) in one pass
+ * over the same hidden states: the predictor reads the tensor that the previous layer's own gate
+ * reads (Sec. 4.2), so the two gates can be stacked into one operand.  Results are those of
+ * probe_route_topk(x, w_gate, bias, ...) and probe_predict_topk(x, w_gate_next, bias_next, ...) up to
+ * fp32 summation order; x is read once and the split-K partial sums are half as many.
+ * Both biases use the same bias_groups / tokens_per_group; either may be NULL.  pred_probs and probs
+ * may be NULL.  Limits as probe_route_topk.
+ */
+size_t probe_route_predict_topk_workspace_bytes(int T, int H, int E, int k);
+
+int probe_route_predict_topk(const void* x_bf16, const float* w_gate, const float* bias,
+                             const float* w_gate_next, const float* bias_next, int bias_groups,
+                             int tokens_per_group, int T, int H, int E, int k, int renormalize,
+                             int32_t* topk_idx, float* topk_w, float* probs, int32_t* expert_counts,
+                             int32_t* pred_idx, float* pred_w, float* pred_probs, int32_t* pred_counts,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---------------------------------------------------------------------------- planner ---
  *
  * Greedy balance-optimal planning (Sec. 4.3, Algorithm 1) on the device: from the all-gathered

@@ -26,8 +26,9 @@ namespace probe {
 constexpr int GBM = 128, GBN = 128, GBK = 64;
 
 // ---- 1. split -------------------------------------------------------------------------
+// planes + plane_stride * p is plane p; `planes` already points at this gate's rows inside a plane
 __global__ __launch_bounds__(256) void gate_split_kernel(const float* __restrict__ w, long n,
-                                                         bf16_t* __restrict__ planes,
+                                                         bf16_t* __restrict__ planes, long plane_stride,
                                                          int32_t* __restrict__ counts, int E) {
   long gid = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x;
   if (counts && gid < E) counts[gid] = 0;
@@ -39,8 +40,8 @@ __global__ __launch_bounds__(256) void gate_split_kernel(const float* __restrict
   float r2 = r1 - bf16_to_f32(mid);  // exact
   bf16_t lo = f32_to_bf16(r2);
   planes[gid] = hi;
-  planes[n + gid] = mid;
-  planes[2 * n + gid] = lo;
+  planes[plane_stride + gid] = mid;
+  planes[2 * plane_stride + gid] = lo;
 }
 
 // ---- 2. gemm --------------------------------------------------------------------------
@@ -275,9 +276,10 @@ __device__ __forceinline__ int row_min_i(int v) {
 // logit with the same expression as its probability, so both agree bit for bit.
 template <int NV>
 __global__ __launch_bounds__(256) void gate_softmax_topk_kernel(
-    const float* __restrict__ partial, int KS, const float* __restrict__ bias, int G, int tpg, int T,
+    const float* __restrict__ partial, int ld, int KS, const float* __restrict__ bias, int G, int tpg, int T,
     int E, int k, int renorm, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
     float* __restrict__ probs, int32_t* __restrict__ counts) {
+  // `partial` points at this gate's first column; a row of a partial plane has ld entries
   constexpr int U = 2, NL = NV * 4;
   __shared__ int32_t hist[PROBE_MAX_EXPERTS];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -285,7 +287,7 @@ __global__ __launch_bounds__(256) void gate_softmax_topk_kernel(
   hist[tid] = 0;
   __syncthreads();
   const float ninf = -__builtin_inff(), fmin_ = -3.402823466e38f;
-  const bool vec = (E & 3) == 0;
+  const bool vec = (E & 3) == 0 && (ld & 3) == 0;
   const int tokens_per_pass = gridDim.x * 16 * U;
   for (int t0 = ((blockIdx.x * 4 + wv) * U) * 4 + grp; t0 < T; t0 += tokens_per_pass) {
     // token u of this row is t0 + 4u; the rows of a wave are independent under DPP row operations
@@ -314,7 +316,7 @@ __global__ __launch_bounds__(256) void gate_softmax_topk_kernel(
 #pragma unroll
             for (int i = 0; i < NV; ++i) {
               const int e0 = min(64 * i + 4 * sub, E - 4);
-              tmp[r][u][i] = *reinterpret_cast<const float4*>(partial + (static_cast<long>(q) * T + tt[u]) * E + e0);
+              tmp[r][u][i] = *reinterpret_cast<const float4*>(partial + (static_cast<long>(q) * T + tt[u]) * ld + e0);
             }
         }
 #pragma unroll
@@ -354,7 +356,7 @@ __global__ __launch_bounds__(256) void gate_softmax_topk_kernel(
           const int e = 64 * (i >> 2) + 4 * sub + (i & 3);
           float sacc = 0.f;
           if (e < E) {
-            for (int q = 0; q < KS; ++q) sacc += partial[(static_cast<long>(q) * T + tt[u]) * E + e];
+            for (int q = 0; q < KS; ++q) sacc += partial[(static_cast<long>(q) * T + tt[u]) * ld + e];
             if (bias) sacc += bias[static_cast<long>(g) * E + e];
           }
           l[u][i] = sacc;
@@ -668,7 +670,7 @@ static int route_impl(const char* name, const void* x_bf16, const float* w_gate,
   if (T == 0) n = 0;  // nothing to route: only the counts are cleared
   long split_threads = n > E ? n : E;
   hipLaunchKernelGGL(gate_split_kernel, dim3(static_cast<unsigned>((split_threads + 255) / 256)), dim3(256),
-                     0, st, w_gate, n, planes, expert_counts, E);
+                     0, st, w_gate, n, planes, n, expert_counts, E);
   if (T > 0) {
     launch_gate_gemm<3>(sh, st, x, planes, T, H, E, partial);
     int planes_to_sum = sh.ks;
@@ -694,7 +696,7 @@ static int route_impl(const char* name, const void* x_bf16, const float* w_gate,
     if (grid > 4096) grid = 4096;
     int G = bias ? bias_groups : 1, tpg = bias ? tokens_per_group : 1;
 #define PROBE_TOPK_LAUNCH(V)                                                                               \
-  hipLaunchKernelGGL(gate_softmax_topk_kernel<V>, dim3(grid), dim3(256), 0, st, partial, planes_to_sum, bias, \
+  hipLaunchKernelGGL(gate_softmax_topk_kernel<V>, dim3(grid), dim3(256), 0, st, partial, E, planes_to_sum, bias, \
                      G, tpg, T, E, k, renormalize ? 1 : 0, topk_idx, topk_w, probs, expert_counts)
     if (E <= 64) {
       PROBE_TOPK_LAUNCH(1);
@@ -704,6 +706,74 @@ static int route_impl(const char* name, const void* x_bf16, const float* w_gate,
       PROBE_TOPK_LAUNCH(4);
     }
 #undef PROBE_TOPK_LAUNCH
+  }
+  return check_launch(name);
+}
+
+// Router of layer L-1 and zero-residual predictor of layer L on the same hidden states in one pass:
+// the two gates are stacked into one operand of 2E rows per plane, one GEMM produces both sets of
+// logits (x is read once, half as many split-K slices), the softmax / top-k kernel runs once per
+// gate on its half of the columns.
+static int route_predict_impl(const void* x_bf16, const float* w_gate, const float* bias,
+                              const float* w_gate_next, const float* bias_next, int bias_groups,
+                              int tokens_per_group, int T, int H, int E, int k, int renormalize,
+                              int32_t* topk_idx, float* topk_w, float* probs, int32_t* expert_counts,
+                              int32_t* pred_idx, float* pred_w, float* pred_probs, int32_t* pred_counts,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+  const char* name = "probe_route_predict_topk";
+  PROBE_REQUIRE(T >= 0 && H > 0 && E > 0 && k > 0 && k <= E, PROBE_EINVAL,
+                "%s: bad dims T=%d H=%d E=%d k=%d", name, T, H, E, k);
+  PROBE_REQUIRE((bias == nullptr && bias_next == nullptr) || (bias_groups >= 1 && tokens_per_group >= 1),
+                PROBE_EINVAL, "%s: bias_groups=%d tokens_per_group=%d", name, bias_groups, tokens_per_group);
+  PROBE_REQUIRE(E <= PROBE_MAX_EXPERTS && k <= PROBE_MAX_TOPK && H % 8 == 0, PROBE_EUNSUPPORTED,
+                "%s: needs E <= %d, k <= %d, H %% 8 == 0 (E=%d k=%d H=%d)", name, PROBE_MAX_EXPERTS,
+                PROBE_MAX_TOPK, E, k, H);
+  PROBE_REQUIRE(w_gate != nullptr && w_gate_next != nullptr, PROBE_EINVAL, "%s: a gate is NULL", name);
+  PROBE_REQUIRE(T == 0 || (x_bf16 && topk_idx && topk_w && pred_idx && pred_w), PROBE_EINVAL,
+                "%s: null pointer", name);
+  PROBE_REQUIRE(aligned16(x_bf16) && aligned16(w_gate) && aligned16(w_gate_next), PROBE_EALIGN,
+                "%s: x and the gates must be 16-byte aligned", name);
+  RouteLayout L = route_layout(T, H, 2 * E, 0);
+  const RouteShape& sh = L.gate;
+  PROBE_REQUIRE(workspace && aligned16(workspace) && workspace_bytes >= L.total, PROBE_EWORKSPACE,
+                "%s: workspace too small or misaligned (%zu < %zu)", name, workspace_bytes, L.total);
+  if (T > 0 && sh.dma) {
+    int rc = gate_prepare();
+    if (rc != PROBE_OK) return rc;
+  }
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  bf16_t* planes = static_cast<bf16_t*>(workspace);  // [3][2E][H]: rows 0..E-1 this layer's gate, E..2E-1 the next
+  float* partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + sh.planes_bytes);
+  long n = static_cast<long>(E) * H;
+  if (T == 0) n = 0;
+  const long split_threads = n > E ? n : E;
+  const unsigned split_grid = static_cast<unsigned>((split_threads + 255) / 256);
+  hipLaunchKernelGGL(gate_split_kernel, dim3(split_grid), dim3(256), 0, st, w_gate, n, planes, 2 * n,
+                     expert_counts, E);
+  hipLaunchKernelGGL(gate_split_kernel, dim3(split_grid), dim3(256), 0, st, w_gate_next, n, planes + n, 2 * n,
+                     pred_counts, E);
+  if (T > 0) {
+    launch_gate_gemm<3>(sh, st, static_cast<const bf16_t*>(x_bf16), planes, T, H, 2 * E, partial);
+    int grid = (T + 31) / 32;
+    if (grid > 4096) grid = 4096;
+    const int G1 = bias ? bias_groups : 1, tpg1 = bias ? tokens_per_group : 1;
+    const int G2 = bias_next ? bias_groups : 1, tpg2 = bias_next ? tokens_per_group : 1;
+    const int rn = renormalize ? 1 : 0;
+#define PROBE_TOPK_LAUNCH2(V)                                                                                     \
+  do {                                                                                                            \
+    hipLaunchKernelGGL(gate_softmax_topk_kernel<V>, dim3(grid), dim3(256), 0, st, partial, 2 * E, sh.ks, bias, G1, \
+                       tpg1, T, E, k, rn, topk_idx, topk_w, probs, expert_counts);                                \
+    hipLaunchKernelGGL(gate_softmax_topk_kernel<V>, dim3(grid), dim3(256), 0, st, partial + E, 2 * E, sh.ks,      \
+                       bias_next, G2, tpg2, T, E, k, rn, pred_idx, pred_w, pred_probs, pred_counts);              \
+  } while (0)
+    if (E <= 64) {
+      PROBE_TOPK_LAUNCH2(1);
+    } else if (E <= 128) {
+      PROBE_TOPK_LAUNCH2(2);
+    } else {
+      PROBE_TOPK_LAUNCH2(4);
+    }
+#undef PROBE_TOPK_LAUNCH2
   }
   return check_launch(name);
 }
@@ -759,4 +829,22 @@ extern "C" int probe_predict_topk_residual(const void* h_prev_bf16, const float*
   return probe::route_impl("probe_predict_topk_residual", h_prev_bf16, w_gate_next, bias_next, bias_groups,
                            tokens_per_group, w1_hat_bf16, w2_hat, D, T, H, E, k, renormalize, pred_idx, pred_w,
                            probs, pred_counts, workspace, workspace_bytes, stream);
+}
+
+extern "C" size_t probe_route_predict_topk_workspace_bytes(int T, int H, int E, int k) {
+  (void)k;
+  if (T < 0 || H <= 0 || E <= 0) return 0;
+  return probe::route_layout(T, H, 2 * E, 0).total;
+}
+
+extern "C" int probe_route_predict_topk(const void* x_bf16, const float* w_gate, const float* bias,
+                                        const float* w_gate_next, const float* bias_next, int bias_groups,
+                                        int tokens_per_group, int T, int H, int E, int k, int renormalize,
+                                        int32_t* topk_idx, float* topk_w, float* probs, int32_t* expert_counts,
+                                        int32_t* pred_idx, float* pred_w, float* pred_probs,
+                                        int32_t* pred_counts, void* workspace, size_t workspace_bytes,
+                                        void* stream) {
+  return probe::route_predict_impl(x_bf16, w_gate, bias, w_gate_next, bias_next, bias_groups, tokens_per_group, T,
+                                   H, E, k, renormalize, topk_idx, topk_w, probs, expert_counts, pred_idx, pred_w,
+                                   pred_probs, pred_counts, workspace, workspace_bytes, stream);
 }

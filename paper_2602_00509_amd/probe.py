@@ -69,6 +69,11 @@ def lib():
         L.probe_grouped_ffn.argtypes = ([C.c_void_p] * 4 + [C.c_int] * 4 + [C.c_void_p] * 2 +
                                         [C.c_size_t, C.c_void_p])
         L.probe_combine.argtypes = [C.c_void_p] * 3 + [C.c_int] * 3 + [C.c_void_p] * 2
+        L.probe_route_predict_topk_workspace_bytes.restype = C.c_size_t
+        L.probe_route_predict_topk_workspace_bytes.argtypes = [C.c_int] * 4
+        L.probe_route_predict_topk.restype = C.c_int
+        L.probe_route_predict_topk.argtypes = ([C.c_void_p] * 5 + [C.c_int] * 7 + [C.c_void_p] * 9 +
+                                               [C.c_size_t, C.c_void_p])
         L.probe_plan_greedy_workspace_bytes.restype = C.c_size_t
         L.probe_plan_greedy_workspace_bytes.argtypes = [C.c_int, C.c_int]
         L.probe_plan_greedy.restype = C.c_int
@@ -190,6 +195,55 @@ def predict_topk_residual(h_prev, w_gate_next, bias_next, tokens_per_group, w1_h
     """probe_predict_topk_residual: Eq. 7 in full; w1_hat bf16 [D,H], w2_hat fp32 [E,D]."""
     return _route(lib().probe_predict_topk_residual, h_prev, w_gate_next, bias_next, tokens_per_group, k,
                   renormalize, want_probs, want_counts, out, workspace, stream, residual=(w1_hat, w2_hat))
+
+
+def route_predict_topk_workspace_bytes(T, H, E, k):
+    return int(lib().probe_route_predict_topk_workspace_bytes(T, H, E, k))
+
+
+def route_predict_topk(x, w_gate, bias, w_gate_next, bias_next, tokens_per_group=None, k=2, renormalize=True, *,
+                       want_probs=False, out=None, pred_out=None, workspace=None, stream=None):
+    """probe_route_predict_topk: router and zero-residual predictor of the next layer in one pass over x.
+
+    Returns (route dict, predict dict), each with idx, w, counts and optionally probs."""
+    T, H = x.shape
+    E = w_gate.shape[0]
+    _want(x, torch.bfloat16, (T, H), "x")
+    _want(w_gate, torch.float32, (E, H), "w_gate")
+    _want(w_gate_next, torch.float32, (E, H), "w_gate_next")
+    G = 1
+    biases = []
+    for b in (bias, bias_next):
+        if b is not None:
+            if b.dim() == 1:
+                b = b.view(1, E)
+            G = b.shape[0]
+            _want(b, torch.float32, (G, E), "bias")
+        biases.append(b)
+    if biases[0] is not None and biases[1] is not None:
+        assert biases[0].shape == biases[1].shape
+    tpg = int(tokens_per_group) if tokens_per_group else max(T, 1)
+    dev = x.device
+    outs = []
+    for o in (out, pred_out):
+        o = dict(o) if o else {}
+        o.setdefault("idx", torch.empty((T, k), dtype=torch.int32, device=dev))
+        o.setdefault("w", torch.empty((T, k), dtype=torch.float32, device=dev))
+        o.setdefault("counts", torch.empty((E,), dtype=torch.int32, device=dev))
+        if want_probs:
+            o.setdefault("probs", torch.empty((T, E), dtype=torch.float32, device=dev))
+        _want(o["idx"], torch.int32, (T, k), "idx")
+        _want(o["w"], torch.float32, (T, k), "w")
+        outs.append(o)
+    r, p = outs
+    workspace = _ws(workspace, route_predict_topk_workspace_bytes(T, H, E, k), dev)
+    rc = lib().probe_route_predict_topk(
+        _ptr(x), _ptr(w_gate), _ptr(biases[0]), _ptr(w_gate_next), _ptr(biases[1]), G, tpg, T, H, E, k,
+        int(bool(renormalize)), _ptr(r["idx"]), _ptr(r["w"]), _ptr(r.get("probs") if want_probs else None),
+        _ptr(r["counts"]), _ptr(p["idx"]), _ptr(p["w"]), _ptr(p.get("probs") if want_probs else None),
+        _ptr(p["counts"]), _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(rc)
+    return r, p
 
 
 # ------------------------------------------------------------------------------ planner

@@ -88,3 +88,32 @@ def test_predictor_with_residual_at_the_benchmark_shape(oracle, probe, G):
     np.testing.assert_allclose(g["probs"].cpu().numpy()[tok], o["probs"], rtol=0, atol=G.PROB_ATOL)
     idx = g["idx"].cpu().numpy()
     np.testing.assert_array_equal(g["counts"].cpu().numpy(), np.bincount(idx.ravel(), minlength=E))
+
+
+@pytest.mark.parametrize("T,H,E,k", [(300, 128, 64, 4), (2100, 256, 256, 8), (8200, 512, 128, 8), (150, 72, 9, 3)])
+def test_fused_router_and_predictor_match_their_oracles(oracle, probe, G, T, H, E, k):
+    """One pass over x for this layer's router and the next layer's (zero-residual) predictor: each output
+    set against the oracle of its own gate, and against the two separate calls (same decisions)."""
+    print("case fused T=%d H=%d E=%d" % (T, H, E), flush=True)
+    rng = np.random.default_rng(T)
+    x = wl.f32_to_bf16_bits(rng.standard_normal((T, H), dtype=np.float32))
+    w1 = rng.standard_normal((E, H), dtype=np.float32) * np.float32(0.05)
+    w2 = rng.standard_normal((E, H), dtype=np.float32) * np.float32(0.05)
+    b1 = rng.standard_normal((2, E)).astype(np.float32)
+    b2 = rng.standard_normal((2, E)).astype(np.float32)
+    tpg = (T + 1) // 2
+    dx = G.dev_bf16(x)
+    d = lambda a: torch.from_numpy(a).cuda()
+    r, p = probe.route_predict_topk(dx, d(w1), d(b1), d(w2), d(b2), tpg, k, True, want_probs=True)
+    torch.cuda.synchronize()
+    for got, w, b in ((r, w1, b1), (p, w2, b2)):
+        o = oracle.route_topk(x, w, b, tpg, k, True)
+        G.check_route(got, o, k, True)
+        np.testing.assert_allclose(got["probs"].cpu().numpy(), o["probs"], rtol=0, atol=G.PROB_ATOL)
+        np.testing.assert_array_equal(got["counts"].cpu().numpy(),
+                                      np.bincount(got["idx"].cpu().numpy().ravel(), minlength=E))
+    # a missing bias on one side only
+    r2, p2 = probe.route_predict_topk(dx, d(w1), None, d(w2), d(b2), tpg, k, False)
+    torch.cuda.synchronize()
+    G.check_route(r2, oracle.route_topk(x, w1, None, tpg, k, False), k, False)
+    G.check_route(p2, oracle.route_topk(x, w2, b2, tpg, k, False), k, False)
