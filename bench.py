@@ -49,6 +49,8 @@ def main():
     ap.add_argument("--fused-route-predict", action="store_true",
                     help="one probe_route_predict_topk call instead of predict_topk + route_topk (the predictor of "
                          "the next layer reads the same hidden states as this layer's router)")
+    ap.add_argument("--gather-on-load", action="store_true",
+                    help="probe_permute without the row copy + probe_grouped_ffn_gather (no xp is written or read)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -117,6 +119,7 @@ def main():
                     pair_row=torch.empty((T, k), dtype=torch.int32, device=dev),
                     xp=torch.empty((N, H), dtype=torch.bfloat16, device=dev),
                     n_local=torch.empty((1,), dtype=torch.int32, device=dev))
+    perm_lean = {kk: v for kk, v in perm_out.items() if kk != "xp"}
     y = torch.empty((N, H), dtype=torch.bfloat16, device=dev)
     out = torch.empty((T, H), dtype=torch.bfloat16, device=dev)
 
@@ -158,9 +161,15 @@ def main():
             mark(1)
             probe.route_topk(d_xs[b], d_wg, d_bias[b], tpg, k, True, out=r_out, workspace=ws_route)
         mark(2)
-        probe.permute(r_out["idx"], d_plans[b], d_xs[b], out=perm_out, workspace=ws_perm)
-        mark(3)
-        probe.grouped_ffn(perm_out["xp"], perm_out["slot_offsets"], tables[b], out=y, workspace=ws_ffn)
+        if args.gather_on_load:
+            probe.permute(r_out["idx"], d_plans[b], d_xs[b], out=perm_lean, workspace=ws_perm, copy_rows=False)
+            mark(3)
+            probe.grouped_ffn_gather(d_xs[b], perm_out["row_pair"], k, perm_out["slot_offsets"], tables[b], out=y,
+                                     workspace=ws_ffn)
+        else:
+            probe.permute(r_out["idx"], d_plans[b], d_xs[b], out=perm_out, workspace=ws_perm)
+            mark(3)
+            probe.grouped_ffn(perm_out["xp"], perm_out["slot_offsets"], tables[b], out=y, workspace=ws_ffn)
         mark(4)
         probe.combine(y, perm_out["pair_row"], r_out["w"], out=out)
         mark(5)
@@ -216,7 +225,8 @@ def main():
                    "step": ("route_predict_topk (stage time reported under predict, route = 0)"
                             if args.fused_route_predict else
                             ("predict_topk_residual(D=%d)" % D if D else "predict_topk") + " + route_topk") +
-                           " + permute + grouped_ffn + combine",
+                           (" + permute (index outputs only) + grouped_ffn_gather + combine" if args.gather_on_load
+                            else " + permute + grouped_ffn + combine"),
                    "rows_per_step_mean": nl_mean, "active_slots_mean": act_mean},
         "stage_ms": mean_ms,
         "stage_ms_min": {n: float(np.min(v)) for n, v in stage_ms.items()},

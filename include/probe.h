@@ -156,7 +156,8 @@ typedef struct {
  *   row_pair      device, int32 [T*k]  (out) pair of each row; entries >= n_local are -1
  *   pair_row      device, int32 [T,k]  (out) row of each pair, -1 = computed on another GPU
  *   xp_bf16       device, bf16 [T*k,H] (out) xp[row] = x[row_pair[row] / k]; rows >= n_local
- *                 are not written
+ *                 are not written.  May be NULL: then no row is copied (for callers that gather
+ *                 the rows on load, probe_grouped_ffn_gather) and x_bf16 is not read
  *   n_local       device, int32 [1]    (out)
  *
  * Integer outputs and row copies are exact.  Limits: E <= 256, k <= 8, S <= 1024, H % 8 == 0,
@@ -194,6 +195,20 @@ int probe_grouped_ffn(const void* xp_bf16, const int32_t* slot_offsets,
                       const void* const* w13_ptrs, const void* const* w2_ptrs, int S, int H,
                       int F, int max_rows, void* y_bf16, void* workspace,
                       size_t workspace_bytes, void* stream);
+
+/* The same FFN with its activation rows gathered on load: row r of the row space is
+ * x[row_pair[r] / k], read straight from the token rows while the first GEMM fills its tiles, so the
+ * permuted copy xp is never written or read (call probe_permute with xp_bf16 = NULL: it then
+ * produces its index outputs only).  Output and arithmetic are those of probe_grouped_ffn on
+ * xp = gather(x).
+ *   x_bf16    device, bf16 [T,H]
+ *   row_pair  device, int32 [max_rows] as written by probe_permute (entries >= n_local are not read)
+ * Additional limit: x below 2 GiB.
+ */
+int probe_grouped_ffn_gather(const void* x_bf16, const int32_t* row_pair, int T, int k,
+                             const int32_t* slot_offsets, const void* const* w13_ptrs,
+                             const void* const* w2_ptrs, int S, int H, int F, int max_rows,
+                             void* y_bf16, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------- combine ---
  *

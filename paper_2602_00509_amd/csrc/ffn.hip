@@ -238,18 +238,35 @@ static int ffn_grid(int max_tiles, int n_cols) {
 }
 
 // ---- 1. gemm1 + SwiGLU ----------------------------------------------------------------
-template <int MI>
-__device__ __forceinline__ void gemm1_tile(const bf16_t* __restrict__ xp, const bf16_t* __restrict__ w13,
+// Where the activation rows of gemm1 come from: the permuted copy xp (row r of the row space), or,
+// gathered on load, the token rows themselves: row r is x[row_pair[r] / k] (no xp is ever written).
+struct RowSource {
+  const bf16_t* base;         // xp, or x when gathering
+  const int32_t* row_pair;    // nullptr = rows are stored in row-space order
+  int k, n_tokens;
+};
+
+template <int MI, bool GATHER>
+__device__ __forceinline__ void gemm1_tile(const RowSource& src, const bf16_t* __restrict__ w13,
                                            int row0, int rows, int n0, int H, int F,
                                            bf16_t* __restrict__ hbuf, u32x4* smem) {
   // rows = valid rows from row0 to the end of the slot (may exceed the tile height)
   const int lane = threadIdx.x & 63;
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wv / 4, wn = wv % 4;
-  __amdgpu_buffer_rsrc_t rA = make_rsrc(xp + static_cast<size_t>(row0) * H, static_cast<size_t>(rows) * H * 2);
+  __amdgpu_buffer_rsrc_t rA =
+      GATHER ? make_rsrc(src.base, static_cast<size_t>(src.n_tokens) * H * 2)
+             : make_rsrc(src.base + static_cast<size_t>(row0) * H, static_cast<size_t>(rows) * H * 2);
   __amdgpu_buffer_rsrc_t rB = make_rsrc(w13, static_cast<size_t>(2) * F * H * 2);
   int voff[MI + 4];
-  dma_offsets<MI>(wv, lane, H * 2, [&](int r) { return min(r, rows - 1); }, voff);
+  dma_offsets<MI>(wv, lane, H * 2,
+                  [&](int r) {
+                    const int rr = min(r, rows - 1);
+                    if (!GATHER) return rr;
+                    const int pair = src.row_pair[row0 + rr];  // a valid row always names a pair
+                    return min(max(pair, 0) / src.k, src.n_tokens - 1);
+                  },
+                  voff);
   // weight tile row j: wave column block q = j / 64; inside it 32 gate rows, then the 32 up rows
   dma_offsets<4>(wv, lane, H * 2,
                  [&](int j) {
@@ -295,9 +312,9 @@ __device__ __forceinline__ void gemm1_tile(const bf16_t* __restrict__ xp, const 
 
 // one-dimensional launch over (row tile, column block) work items; a column block is 128 gate +
 // 128 up weight rows
-__global__ __launch_bounds__(512, 2) void ffn_gemm1_kernel(const bf16_t* __restrict__ xp,
-                                                           const int32_t* __restrict__ table, int H, int F,
-                                                           bf16_t* __restrict__ hbuf) {
+template <bool GATHER>
+__global__ __launch_bounds__(512, 2) void ffn_gemm1_kernel(RowSource src, const int32_t* __restrict__ table, int H,
+                                                           int F, bf16_t* __restrict__ hbuf) {
 #if defined(__HIP_DEVICE_COMPILE__)
   extern __shared__ u32x4 smem[];
   int tile, col;
@@ -306,15 +323,15 @@ __global__ __launch_bounds__(512, 2) void ffn_gemm1_kernel(const bf16_t* __restr
   const int n0 = col * 128;
   const bf16_t* w13 = static_cast<const bf16_t*>(e.w13);
   if (e.height > 256)
-    gemm1_tile<5>(xp, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
+    gemm1_tile<5, GATHER>(src, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
   else if (e.height > 192)
-    gemm1_tile<4>(xp, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
+    gemm1_tile<4, GATHER>(src, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
   else if (e.height > 128)
-    gemm1_tile<3>(xp, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
+    gemm1_tile<3, GATHER>(src, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
   else if (e.height > 64)
-    gemm1_tile<2>(xp, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
+    gemm1_tile<2, GATHER>(src, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
   else
-    gemm1_tile<1>(xp, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
+    gemm1_tile<1, GATHER>(src, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
 #endif
 }
 
@@ -407,8 +424,11 @@ static int ffn_prepare() {
   }
   std::lock_guard<std::mutex> lock(mu);
   if (done[dev]) return PROBE_OK;
-  hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(ffn_gemm1_kernel),
+  hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(ffn_gemm1_kernel<false>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kFfnLdsBytes);
+  if (err == hipSuccess)
+    err = hipFuncSetAttribute(reinterpret_cast<const void*>(ffn_gemm1_kernel<true>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, kFfnLdsBytes);
   if (err == hipSuccess)
     err = hipFuncSetAttribute(reinterpret_cast<const void*>(ffn_gemm2_kernel),
                               hipFuncAttributeMaxDynamicSharedMemorySize, kFfnLdsBytes);
@@ -429,32 +449,39 @@ extern "C" size_t probe_grouped_ffn_workspace_bytes(int S, int H, int F, int max
   return s.h_bytes + s.table_bytes;
 }
 
-extern "C" int probe_grouped_ffn(const void* xp_bf16, const int32_t* slot_offsets,
-                                 const void* const* w13_ptrs, const void* const* w2_ptrs, int S,
-                                 int H, int F, int max_rows, void* y_bf16, void* workspace,
-                                 size_t workspace_bytes, void* stream) {
-  using namespace probe;
+namespace probe {
+
+// Shared body of probe_grouped_ffn (row_pair == nullptr: activations from xp) and
+// probe_grouped_ffn_gather (activations gathered from the token rows through row_pair).
+static int ffn_impl(const char* name, const void* act_bf16, const int32_t* row_pair, int k, int T,
+                    const int32_t* slot_offsets, const void* const* w13_ptrs, const void* const* w2_ptrs, int S,
+                    int H, int F, int max_rows, void* y_bf16, void* workspace, size_t workspace_bytes,
+                    void* stream) {
   PROBE_REQUIRE(S >= 1 && H > 0 && F > 0 && max_rows >= 0, PROBE_EINVAL,
-                "probe_grouped_ffn: bad dims S=%d H=%d F=%d max_rows=%d", S, H, F, max_rows);
+                "%s: bad dims S=%d H=%d F=%d max_rows=%d", name, S, H, F, max_rows);
   PROBE_REQUIRE(S <= PROBE_MAX_SLOTS && H % 64 == 0 && F % 64 == 0, PROBE_EUNSUPPORTED,
-                "probe_grouped_ffn: needs S <= %d, H %% 64 == 0, F %% 64 == 0 (S=%d H=%d F=%d)",
-                PROBE_MAX_SLOTS, S, H, F);
+                "%s: needs S <= %d, H %% 64 == 0, F %% 64 == 0 (S=%d H=%d F=%d)", name, PROBE_MAX_SLOTS, S, H, F);
   PROBE_REQUIRE(static_cast<size_t>(2) * F * H * 2 <= 0x7fffffffull, PROBE_EUNSUPPORTED,
-                "probe_grouped_ffn: one expert's w13 must stay below 2 GiB (H=%d F=%d)", H, F);
+                "%s: one expert's w13 must stay below 2 GiB (H=%d F=%d)", name, H, F);
   PROBE_REQUIRE(H <= (1 << 21) && F <= (1 << 21), PROBE_EUNSUPPORTED,
-                "probe_grouped_ffn: H and F must not exceed 2^21 (32-bit byte offsets inside a row tile)");
-  if (max_rows == 0) return PROBE_OK;
-  PROBE_REQUIRE(xp_bf16 && slot_offsets && w13_ptrs && w2_ptrs && y_bf16, PROBE_EINVAL,
-                "probe_grouped_ffn: null pointer");
-  PROBE_REQUIRE(aligned16(xp_bf16) && aligned16(y_bf16), PROBE_EALIGN,
-                "probe_grouped_ffn: xp/y must be 16-byte aligned");
+                "%s: H and F must not exceed 2^21 (32-bit byte offsets inside a row tile)", name);
+  const bool gather = row_pair != nullptr;
+  if (gather) {
+    PROBE_REQUIRE(k >= 1 && k <= PROBE_MAX_TOPK && T >= 0, PROBE_EINVAL, "%s: bad k=%d or T=%d", name, k, T);
+    PROBE_REQUIRE(static_cast<size_t>(T) * H * 2 <= 0x7fffffffull, PROBE_EUNSUPPORTED,
+                  "%s: x must stay below 2 GiB (T=%d H=%d)", name, T, H);
+  }
+  if (max_rows == 0 || (gather && T == 0)) return PROBE_OK;
+  PROBE_REQUIRE(act_bf16 && slot_offsets && w13_ptrs && w2_ptrs && y_bf16, PROBE_EINVAL, "%s: null pointer", name);
+  PROBE_REQUIRE(aligned16(act_bf16) && aligned16(y_bf16), PROBE_EALIGN,
+                "%s: activations and y must be 16-byte aligned", name);
   FfnShape sh = ffn_shape(S, F, max_rows);
   PROBE_REQUIRE(workspace && aligned16(workspace) && workspace_bytes >= sh.h_bytes + sh.table_bytes,
-                PROBE_EWORKSPACE, "probe_grouped_ffn: workspace too small or misaligned (%zu < %zu)",
-                workspace_bytes, sh.h_bytes + sh.table_bytes);
+                PROBE_EWORKSPACE, "%s: workspace too small or misaligned (%zu < %zu)", name, workspace_bytes,
+                sh.h_bytes + sh.table_bytes);
   PROBE_REQUIRE(static_cast<long>(sh.max_tiles + 8) * ((F + 127) / 128 + 4) < (1l << 30) &&
                     static_cast<long>(sh.max_tiles + 8) * ((H + 255) / 256 + 4) < (1l << 30),
-                PROBE_EUNSUPPORTED, "probe_grouped_ffn: max_rows too large (%d)", max_rows);
+                PROBE_EUNSUPPORTED, "%s: max_rows too large (%d)", name, max_rows);
   int rc = ffn_prepare();
   if (rc != PROBE_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -462,9 +489,37 @@ extern "C" int probe_grouped_ffn(const void* xp_bf16, const int32_t* slot_offset
   int32_t* table = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + sh.h_bytes);
   hipLaunchKernelGGL(ffn_schedule_kernel, dim3(1), dim3(256), 0, st, slot_offsets, w13_ptrs, w2_ptrs, S, sh.max_tiles,
                      table);
-  hipLaunchKernelGGL(ffn_gemm1_kernel, dim3(ffn_grid(sh.max_tiles, (F + 127) / 128)), dim3(512), kFfnLdsBytes, st,
-                     static_cast<const bf16_t*>(xp_bf16), table, H, F, hbuf);
+  RowSource src;
+  src.base = static_cast<const bf16_t*>(act_bf16);
+  src.row_pair = row_pair;
+  src.k = gather ? k : 1;
+  src.n_tokens = gather ? T : 0;
+  const dim3 grid1(ffn_grid(sh.max_tiles, (F + 127) / 128));
+  if (gather)
+    hipLaunchKernelGGL(ffn_gemm1_kernel<true>, grid1, dim3(512), kFfnLdsBytes, st, src, table, H, F, hbuf);
+  else
+    hipLaunchKernelGGL(ffn_gemm1_kernel<false>, grid1, dim3(512), kFfnLdsBytes, st, src, table, H, F, hbuf);
   hipLaunchKernelGGL(ffn_gemm2_kernel, dim3(ffn_grid(sh.max_tiles, (H + FBN - 1) / FBN)), dim3(512), kFfnLdsBytes, st,
                      hbuf, table, H, F, static_cast<bf16_t*>(y_bf16));
-  return check_launch("probe_grouped_ffn");
+  return check_launch(name);
+}
+
+}  // namespace probe
+
+extern "C" int probe_grouped_ffn(const void* xp_bf16, const int32_t* slot_offsets,
+                                 const void* const* w13_ptrs, const void* const* w2_ptrs, int S,
+                                 int H, int F, int max_rows, void* y_bf16, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+  return probe::ffn_impl("probe_grouped_ffn", xp_bf16, nullptr, 1, 0, slot_offsets, w13_ptrs, w2_ptrs, S, H, F,
+                         max_rows, y_bf16, workspace, workspace_bytes, stream);
+}
+
+extern "C" int probe_grouped_ffn_gather(const void* x_bf16, const int32_t* row_pair, int T, int k,
+                                        const int32_t* slot_offsets, const void* const* w13_ptrs,
+                                        const void* const* w2_ptrs, int S, int H, int F, int max_rows,
+                                        void* y_bf16, void* workspace, size_t workspace_bytes, void* stream) {
+  PROBE_REQUIRE(row_pair != nullptr || max_rows == 0 || T == 0, PROBE_EINVAL,
+                "probe_grouped_ffn_gather: row_pair is NULL");
+  return probe::ffn_impl("probe_grouped_ffn_gather", x_bf16, row_pair, k, T, slot_offsets, w13_ptrs, w2_ptrs, S, H,
+                         F, max_rows, y_bf16, workspace, workspace_bytes, stream);
 }

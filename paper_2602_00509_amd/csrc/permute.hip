@@ -485,7 +485,7 @@ extern "C" int probe_permute(const int32_t* topk_idx, const probe_plan* plan, co
   PROBE_REQUIRE(plan->rep_off && plan->rep_slot && plan->rep_weight, PROBE_EINVAL,
                 "probe_permute: plan array is NULL");
   PROBE_REQUIRE(slot_counts && slot_offsets && n_local, PROBE_EINVAL, "probe_permute: null output");
-  PROBE_REQUIRE(T == 0 || (topk_idx && x_bf16 && row_pair && pair_row && xp_bf16), PROBE_EINVAL,
+  PROBE_REQUIRE(T == 0 || (topk_idx && row_pair && pair_row && (xp_bf16 == nullptr || x_bf16)), PROBE_EINVAL,
                 "probe_permute: null pointer");
   PROBE_REQUIRE(aligned16(x_bf16) && aligned16(xp_bf16), PROBE_EALIGN,
                 "probe_permute: x/xp must be 16-byte aligned");
@@ -512,7 +512,7 @@ extern "C" int probe_permute(const int32_t* topk_idx, const probe_plan* plan, co
                          N, E, seg, plan->rep_off, plan->rep_slot, plan->rep_weight, slot_offsets, S,
                          pair_row, row_pair);
   }
-  if (U > 0) {
+  if (U > 0 && xp_bf16 != nullptr) {  // xp == NULL: the caller gathers rows on load instead
     int cpr = H / 8;
     long total = static_cast<long>(T) * cpr;
     unsigned grid = static_cast<unsigned>((total + 255) / 256);

@@ -68,6 +68,9 @@ def lib():
                                     [C.c_void_p] * 7 + [C.c_size_t, C.c_void_p])
         L.probe_grouped_ffn.argtypes = ([C.c_void_p] * 4 + [C.c_int] * 4 + [C.c_void_p] * 2 +
                                         [C.c_size_t, C.c_void_p])
+        L.probe_grouped_ffn_gather.argtypes = ([C.c_void_p] * 2 + [C.c_int] * 2 + [C.c_void_p] * 3 + [C.c_int] * 4 +
+                                               [C.c_void_p] * 2 + [C.c_size_t, C.c_void_p])
+        L.probe_grouped_ffn_gather.restype = C.c_int
         L.probe_combine.argtypes = [C.c_void_p] * 3 + [C.c_int] * 3 + [C.c_void_p] * 2
         L.probe_route_predict_topk_workspace_bytes.restype = C.c_size_t
         L.probe_route_predict_topk_workspace_bytes.argtypes = [C.c_int] * 4
@@ -296,8 +299,10 @@ def permute_workspace_bytes(T, E, k, S):
     return int(lib().probe_permute_workspace_bytes(T, E, k, S))
 
 
-def permute(topk_idx, plan: Plan, x, *, out=None, workspace=None, stream=None):
-    """probe_permute: returns dict(slot_counts, slot_offsets, row_pair, pair_row, xp, n_local)."""
+def permute(topk_idx, plan: Plan, x, *, out=None, workspace=None, stream=None, copy_rows=True):
+    """probe_permute: returns dict(slot_counts, slot_offsets, row_pair, pair_row, xp, n_local).
+
+    copy_rows=False passes xp = NULL: index outputs only (for grouped_ffn_gather); no "xp" in the result."""
     T, k = topk_idx.shape
     H = x.shape[1]
     E, S = plan.num_experts, plan.num_slots
@@ -309,6 +314,9 @@ def permute(topk_idx, plan: Plan, x, *, out=None, workspace=None, stream=None):
     spec = dict(slot_counts=((S,), torch.int32), slot_offsets=((S + 1,), torch.int32),
                 row_pair=((N,), torch.int32), pair_row=((T, k), torch.int32),
                 xp=((N, H), torch.bfloat16), n_local=((1,), torch.int32))
+    if not copy_rows:
+        del spec["xp"]
+        out.pop("xp", None)
     for name, (shape, dt) in spec.items():
         if name not in out:
             out[name] = torch.empty(shape, dtype=dt, device=dev)
@@ -316,7 +324,7 @@ def permute(topk_idx, plan: Plan, x, *, out=None, workspace=None, stream=None):
     workspace = _ws(workspace, permute_workspace_bytes(T, E, k, S), dev)
     rc = lib().probe_permute(_ptr(topk_idx), C.byref(plan.c), _ptr(x), T, H, E, k,
                              _ptr(out["slot_counts"]), _ptr(out["slot_offsets"]),
-                             _ptr(out["row_pair"]), _ptr(out["pair_row"]), _ptr(out["xp"]),
+                             _ptr(out["row_pair"]), _ptr(out["pair_row"]), _ptr(out.get("xp")),
                              _ptr(out["n_local"]), _ptr(workspace), workspace.numel(),
                              _stream(stream))
     _check(rc)
@@ -359,6 +367,27 @@ def grouped_ffn(xp, slot_offsets, weights: WeightTable, *, out=None, workspace=N
     rc = lib().probe_grouped_ffn(_ptr(xp), _ptr(slot_offsets), _ptr(weights.w13_ptrs),
                                  _ptr(weights.w2_ptrs), S, H, F, max_rows, _ptr(out),
                                  _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(rc)
+    return out
+
+
+def grouped_ffn_gather(x, row_pair, k, slot_offsets, weights: WeightTable, *, out=None, workspace=None,
+                       stream=None):
+    """probe_grouped_ffn_gather: the FFN on rows x[row_pair[r] / k] gathered on load (no xp)."""
+    T, H = x.shape
+    max_rows = row_pair.numel()
+    S, F = weights.S, weights.F
+    _want(x, torch.bfloat16, (T, H), "x")
+    _want(row_pair, torch.int32, (max_rows,), "row_pair")
+    _want(slot_offsets, torch.int32, (S + 1,), "slot_offsets")
+    assert H == weights.H
+    if out is None:
+        out = torch.empty((max_rows, H), dtype=torch.bfloat16, device=x.device)
+    _want(out, torch.bfloat16, (max_rows, H), "y")
+    workspace = _ws(workspace, grouped_ffn_workspace_bytes(S, H, F, max_rows), x.device)
+    rc = lib().probe_grouped_ffn_gather(_ptr(x), _ptr(row_pair), T, k, _ptr(slot_offsets), _ptr(weights.w13_ptrs),
+                                        _ptr(weights.w2_ptrs), S, H, F, max_rows, _ptr(out), _ptr(workspace),
+                                        workspace.numel(), _stream(stream))
     _check(rc)
     return out
 

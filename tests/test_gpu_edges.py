@@ -259,3 +259,33 @@ def test_ffn_every_way_a_slot_is_cut_into_tiles(oracle, probe, G):
     got = G.f64_of(y)
     assert G.rel_err(got[:n], ref) < G.BF16_RTOL
     assert (got[n:] == 7.0).all()          # rows past the last slot are not written
+
+
+@pytest.mark.parametrize("cid", [1, 4])
+def test_ffn_with_rows_gathered_on_load_equals_ffn_on_the_permuted_copy(oracle, probe, G, cid):
+    """probe_permute without the row copy + probe_grouped_ffn_gather give bit for bit the y of the standard
+    pair (same kernels, only the source of the activation rows differs), and match the oracle."""
+    cfg = wl.CONFIGS[cid]
+    L, r = _layer(G, probe, cfg)
+    counts = r["counts"].cpu().numpy()
+    plan = wl.build_plan(cfg, counts)
+    d_plan = probe.Plan(plan["rep_off"], plan["rep_slot"], plan["rep_weight"], plan["num_slots"])
+    full = probe.permute(r["idx"], d_plan, L.d_x)
+    lean = probe.permute(r["idx"], d_plan, L.d_x, copy_rows=False)
+    assert "xp" not in lean
+    for key in ("slot_counts", "slot_offsets", "pair_row", "n_local"):
+        assert torch.equal(full[key], lean[key]), key
+    nl = int(full["n_local"].item())
+    assert torch.equal(full["row_pair"][:nl], lean["row_pair"][:nl])
+    L.load_weights(plan["slot_expert"], probe)
+    y0 = torch.full((cfg.N, cfg.H), 3.0, dtype=torch.bfloat16, device="cuda")
+    y1 = torch.full((cfg.N, cfg.H), 3.0, dtype=torch.bfloat16, device="cuda")
+    probe.grouped_ffn(full["xp"], full["slot_offsets"], L.weights, out=y0)
+    probe.grouped_ffn_gather(L.d_x, lean["row_pair"], cfg.k, lean["slot_offsets"], L.weights, out=y1)
+    torch.cuda.synchronize()
+    assert torch.equal(y0, y1)
+    ws = [wl.expert_weights(cfg, int(e)) for e in plan["slot_expert"]]
+    o_p = oracle.permute(r["idx"].cpu().numpy(), plan["rep_off"], plan["rep_slot"], plan["rep_weight"],
+                         plan["num_slots"], L.x)
+    ref = oracle.grouped_ffn(o_p["xp"], o_p["slot_offsets"], [w[0] for w in ws], [w[1] for w in ws])
+    assert G.rel_err(G.f64_of(y1)[:nl], ref) < G.BF16_RTOL
