@@ -51,6 +51,9 @@ def main():
                          "the next layer reads the same hidden states as this layer's router)")
     ap.add_argument("--gather-on-load", action="store_true",
                     help="probe_permute without the row copy + probe_grouped_ffn_gather (no xp is written or read)")
+    ap.add_argument("--graph", action="store_true",
+                    help="record each batch's step into a HIP graph and time replays (stage times still come from "
+                         "an eager pass)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -189,6 +192,26 @@ def main():
         step(i % nb, events[i])
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
+    if args.graph:
+        # one graph per batch, recorded on a side stream; the timed region replays them
+        graphs = []
+        cap = torch.cuda.Stream()
+        cap.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(cap):
+            for b in range(nb):
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=cap):
+                    step(b)
+                graphs.append(g)
+        torch.cuda.synchronize()
+        for i in range(args.warmup):
+            graphs[i % nb].replay()
+        torch.cuda.synchronize()
+        t_start = time.perf_counter()
+        for i in range(args.steps):
+            graphs[i % nb].replay()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t_start
 
     names = ["predict", "route", "permute", "ffn", "combine"]
     stage_ms = {n: [] for n in names}
@@ -218,7 +241,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": "bf16", "data": "synthetic", "launch": "hip_graph_replay" if args.graph else "eager",
         "config": {"workload": "cfg%d %s: T=%d H=%d E=%d top-%d F=%d, %d native + %d replica slots, Zipf s=%.1f, "
                                "%d rotating batches" % (cfg.cid, cfg.name, T, H, E, k, F, cfg.E_loc, cfg.n_rep,
                                                         cfg.zipf_s, nb),
