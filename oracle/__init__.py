@@ -233,6 +233,19 @@ def moe_layer(x_bits, w_gate, bias, tokens_per_group, k, renormalize, plan, w13_
     return dict(route=r, permute=p, y=y, out=out)
 
 
+def cross_entropy_sum(true_probs, pred_probs) -> float:
+    """Sum over tokens of - sum_e p_true log p_pred (the distillation loss of Sec. 4.2), fp64.
+    Terms with p_true = 0 contribute nothing."""
+    p = np.asarray(true_probs, np.float64)
+    q = np.asarray(pred_probs, np.float64)
+    total = 0.0
+    for t in range(p.shape[0]):
+        for e in range(p.shape[1]):
+            if p[t, e] > 0.0:
+                total -= p[t, e] * np.log(q[t, e])
+    return float(total)
+
+
 # ------------------------------------------------------------------------------ planner
 
 def plan_greedy(n_hat, E_loc, max_replicas=3, budget=3, k_max=16, eps=0, n0=0, g_num=0, g_den=1):

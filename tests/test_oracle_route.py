@@ -218,3 +218,20 @@ def test_residual_matches_torch_fp64(oracle):
     np.testing.assert_allclose(p["logits"], l.numpy(), rtol=0, atol=1e-11)
     np.testing.assert_allclose(p["probs"], torch.softmax(l, 1).numpy(), rtol=0, atol=1e-13)
     assert p["counts"].sum() == T * 4
+
+
+def test_cross_entropy_closed_forms(oracle):
+    """CE(p, p) is the entropy; a one-hot target picks -log q_e; uniform against uniform is log E."""
+    E = 8
+    u = np.full((3, E), 1.0 / E)
+    assert abs(oracle.cross_entropy_sum(u, u) - 3 * np.log(E)) < 1e-12
+    onehot = np.zeros((1, E)); onehot[0, 5] = 1.0
+    q = np.full((1, E), 0.05); q[0, 5] = 0.65
+    assert abs(oracle.cross_entropy_sum(onehot, q) + np.log(0.65)) < 1e-15
+    p = np.array([[0.5, 0.25, 0.25, 0, 0, 0, 0, 0]])
+    assert abs(oracle.cross_entropy_sum(p, np.where(p > 0, p, 1.0)) - 1.5 * np.log(2.0)) < 1e-15      # entropy: 1.5 bits
+    # Gibbs: CE(p, q) >= CE(p, p)
+    rng = np.random.default_rng(0)
+    a, b = rng.random((4, E)), rng.random((4, E))
+    a /= a.sum(1, keepdims=True); b /= b.sum(1, keepdims=True)
+    assert oracle.cross_entropy_sum(a, b) >= oracle.cross_entropy_sum(a, a)
