@@ -273,6 +273,18 @@ def main():
     result["roofline"]["frac_of_measured_mfma_random"] = (
         ffn_tflops / result["roofline"]["peak_measured"]["mfma_only_random_operands_tflops"])
 
+    # the predictor's top-k accuracy: the cloned gate of the next layer on this layer's hidden states against
+    # the same gate on the next layer's hidden states (drifted copies of batch 0; two drift levels)
+    ov = {}
+    for alpha in (0.2, 0.5):
+        d_xn = dev_bf16(wl.drifted_activations(cfg, xs[0], alpha, 0))
+        pr = probe.predict_topk(d_xs[0], d_wg_next, d_bias_next[0], tpg, k, True)
+        tr = probe.route_topk(d_xn, d_wg_next, d_bias_next[0], tpg, k, True)
+        hits, _ = probe.predictor_metrics(pr["idx"], tr["idx"])
+        ov["drift_%.1f" % alpha] = int(hits.item()) / float(T * k)
+        del d_xn
+    result["predictor_topk_overlap"] = ov
+
     # the greedy planner (Algorithm 1) on the device, timed on its own: the batches stand in for the source
     # ranks whose predicted counts an all-gather would deliver; not part of `value`
     ep = cfg.E // cfg.E_loc

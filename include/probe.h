@@ -293,6 +293,23 @@ int probe_plan_greedy(const int32_t* n_hat, int R, int E, int E_loc, int rank,
                       int32_t* moves, int64_t* stats, int32_t* n_assign, void* workspace,
                       size_t workspace_bytes, void* stream);
 
+/* ---------------------------------------------------------------------------- metrics ---
+ *
+ * Evaluation of the lookahead predictor against the router it forecasts (Sec. 4.2, Sec. 6.4); not
+ * on the serving path.
+ *   hits = sum_t |{pred_idx[t,0..kp)} intersect {true_idx[t,0..kt)}|   (int64, exact)
+ *       kp = kt = k: hits / (T k) is the top-k accuracy; kt = k/2: hits / (T k/2) is the top-half-k
+ *       hit rate (true_idx lists a token's experts by descending logit)
+ *   cross_entropy_sum = sum_t - sum_e true_probs[t,e] log pred_probs[t,e]  (fp64, fixed order),
+ *       the loss of the online distillation; NULL to skip (then the probability tensors are not read)
+ *   pred_idx / true_idx  device, int32, row t at t * stride;  pred_probs / true_probs  device, fp32 [T,E]
+ *   hits  device int64 [1],  cross_entropy_sum  device double [1] or NULL
+ */
+int probe_predictor_metrics(const int32_t* pred_idx, int pred_stride, int kp, const int32_t* true_idx,
+                            int true_stride, int kt, int T, const float* pred_probs,
+                            const float* true_probs, int E, int64_t* hits, double* cross_entropy_sum,
+                            void* stream);
+
 /* -------------------------------------------------------------------- measurement aid ---
  *
  * Not a step of the layer.  An MFMA-only loop (v_mfma_f32_32x32x16_bf16, operands in registers, no

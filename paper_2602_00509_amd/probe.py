@@ -82,6 +82,9 @@ def lib():
         L.probe_plan_greedy.restype = C.c_int
         L.probe_plan_greedy.argtypes = ([C.c_void_p] + [C.c_int] * 4 + [C.POINTER(_PlannerParams)] +
                                         [C.c_void_p] * 10 + [C.c_size_t, C.c_void_p])
+        L.probe_predictor_metrics.restype = C.c_int
+        L.probe_predictor_metrics.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int,
+                                              C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
         L.probe_peak_mfma_flops_per_launch.restype = C.c_double
         L.probe_peak_mfma_flops_per_launch.argtypes = [C.c_int, C.c_int]
         L.probe_peak_mfma.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
@@ -416,6 +419,28 @@ probe_predict_topk = predict_topk
 probe_permute = permute
 probe_grouped_ffn = grouped_ffn
 probe_combine = combine
+
+
+def predictor_metrics(pred_idx, true_idx, kp=None, kt=None, pred_probs=None, true_probs=None, *, stream=None):
+    """probe_predictor_metrics: (hits int64 [1], cross-entropy sum float64 [1] or None), on the device.
+
+    hits / (T * kt) with kp = kt = k is the top-k accuracy of the predictor."""
+    T = pred_idx.shape[0]
+    kp = kp or pred_idx.shape[1]
+    kt = kt or true_idx.shape[1]
+    _want(pred_idx, torch.int32, (T, pred_idx.shape[1]), "pred_idx")
+    _want(true_idx, torch.int32, (T, true_idx.shape[1]), "true_idx")
+    hits = torch.empty((1,), dtype=torch.int64, device=pred_idx.device)
+    ce, E = None, 0
+    if pred_probs is not None:
+        E = pred_probs.shape[1]
+        _want(pred_probs, torch.float32, (T, E), "pred_probs")
+        _want(true_probs, torch.float32, (T, E), "true_probs")
+        ce = torch.empty((1,), dtype=torch.float64, device=pred_idx.device)
+    _check(lib().probe_predictor_metrics(_ptr(pred_idx), pred_idx.shape[1], kp, _ptr(true_idx), true_idx.shape[1], kt,
+                                         T, _ptr(pred_probs), _ptr(true_probs), E, _ptr(hits), _ptr(ce),
+                                         _stream(stream)))
+    return hits, ce
 
 
 def peak_mfma(workgroups=256, iters=20000, random_operands=True, *, out=None, stream=None):

@@ -117,3 +117,31 @@ def test_fused_router_and_predictor_match_their_oracles(oracle, probe, G, T, H, 
     torch.cuda.synchronize()
     G.check_route(r2, oracle.route_topk(x, w1, None, tpg, k, False), k, False)
     G.check_route(p2, oracle.route_topk(x, w2, b2, tpg, k, False), k, False)
+
+
+def test_predictor_metrics_match_the_oracle(oracle, probe, G):
+    """Top-k accuracy, top-half-k hit rate (exact integers) and the cross-entropy sum of the predictor
+    against the next layer's router on drifted hidden states; zero drift gives accuracy 1."""
+    cfg = wl.small_config(T=1500, H=128, E=64, k=8, F=128, E_loc=8, n_rep=0, zipf_s=1.5, ep=8, cid=95)
+    T, E, k = cfg.T, cfg.E, cfg.k
+    x = wl.activations(cfg, 0)
+    wg = wl.gate_weights(cfg, 1)
+    b = wl.zipf_bias(cfg, 0, 1)
+    tpg = wl.tokens_per_group(cfg)
+    d = lambda a: torch.from_numpy(a).cuda()
+    for alpha in (0.0, 0.5):
+        x2 = wl.drifted_activations(cfg, x, alpha, 0) if alpha else x
+        pred = probe.predict_topk(G.dev_bf16(x), d(wg), d(b), tpg, k, True, want_probs=True)
+        true = probe.route_topk(G.dev_bf16(x2), d(wg), d(b), tpg, k, True, want_probs=True)
+        hits, ce = probe.predictor_metrics(pred["idx"], true["idx"], pred_probs=pred["probs"], true_probs=true["probs"])
+        half, _ = probe.predictor_metrics(pred["idx"], true["idx"], kp=k, kt=k // 2)
+        torch.cuda.synchronize()
+        pi, ti = pred["idx"].cpu().numpy(), true["idx"].cpu().numpy()
+        assert int(hits) == round(oracle.topk_overlap(pi, ti) * T * k)
+        assert int(half) == round(oracle.topk_overlap(pi, ti[:, : k // 2]) * T * (k // 2))
+        ref = oracle.cross_entropy_sum(true["probs"].cpu().numpy(), pred["probs"].cpu().numpy())
+        assert abs(float(ce) - ref) <= 1e-9 * abs(ref)
+        if alpha == 0.0:
+            assert int(hits) == T * k and int(half) == T * (k // 2)
+        else:
+            assert 0.3 * T * k < int(hits) < T * k
