@@ -162,13 +162,19 @@ __device__ __forceinline__ void gemm_mainloop(__amdgpu_buffer_rsrc_t rA, __amdgp
     cur = (cur + 1 == NST) ? 0 : cur + 1;
   };
   if constexpr (NST == 2) {
-    for (; kt + 2 < KT; advance()) k_step(kt, cur, T_{}, F_{}, T_{});
+    while (kt + 2 < KT) {
+      k_step(kt, cur, T_{}, F_{}, T_{});
+      advance();
+    }
     if (kt + 1 < KT) {
       k_step(kt, cur, F_{}, F_{}, T_{});
       advance();
     }
   } else {
-    for (; kt + 3 < KT; advance()) k_step(kt, cur, T_{}, T_{}, T_{});
+    while (kt + 3 < KT) {
+      k_step(kt, cur, T_{}, T_{}, T_{});
+      advance();
+    }
     if (kt + 2 < KT) {
       k_step(kt, cur, F_{}, T_{}, T_{});
       advance();
