@@ -459,102 +459,70 @@ __global__ __launch_bounds__(256) void gate_softmax_topk_kernel(
 }
 
 // ---- 4. residual of the predictor (Eq. 7) ------------------------------------------------
-// r[t,e] = sum_d w2_hat[e,d] * silu(u[t,d]),  u = W1_hat h summed over its split-K partials, all in
-// fp32 with fixed summation order.  One workgroup takes TOK tokens (32, 16 or 8 so that TOK * D <=
-// 8192): their silu(u) rows go to LDS; w2_hat passes through LDS in slices of 16 columns (coalesced
-// loads, the next slice in flight while the current one is consumed; row stride 20 words).  A thread
-// owns a register tile of 4 experts (lane, lane + 64, ...) x TOK/4 tokens (one token group per
-// wave), so that each 16-byte LDS read feeds several FMAs: the weight reads of sixteen lanes hit
-// sixteen different bank quads, the reads of silu(u) are broadcasts.  r is written as one more
-// "partial" plane of the logits, so the softmax / top-k kernel adds it like a split-K slice.
-constexpr int kResidSlice = 16, kResidStride = 20;
+// r[t,e] = sum_d w2_hat[e,d] * s[t,d],  s = silu(u),  u = W1_hat h summed over its split-K partials.
+// Both factors are fp32; the product runs on the matrix cores at fp32 accuracy by splitting each
+// factor into bf16 planes (hi + mid + lo, as for the gate) and keeping the six largest of the nine
+// plane products: with the planes of s laid side by side along K,
+//     A'[t]   = [ s_hi | s_mid | s_lo ]                         (bf16 [T, 3D])
+//     B'_0[e] = [ w_hi | w_hi  | w_hi ],  B'_1[e] = [ w_mid | w_mid | 0 ],  B'_2[e] = [ w_lo | 0 | 0 ]
+// the three-plane GEMM of the gate computes  s_hi (w_hi + w_mid + w_lo) + s_mid (w_hi + w_mid) + s_lo w_hi;
+// the dropped products are below 2^-24 of the result.  Its split-K slices are written behind the
+// gate's own, so the softmax / top-k kernel adds the residual like further slices of the logits.
+__global__ __launch_bounds__(256) void resid_silu_split_kernel(const float* __restrict__ upartial, int KS2, int T,
+                                                               int D, bf16_t* __restrict__ a_planes) {
+  // one thread per 8 consecutive hidden units of one token
+  const long gid = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x;
+  const int groups = D / 8;
+  if (gid >= static_cast<long>(T) * groups) return;
+  const int t = static_cast<int>(gid / groups), d0 = static_cast<int>(gid % groups) * 8;
+  float u[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) u[j] = 0.f;
+  for (int q = 0; q < KS2; ++q) {
+    const float4* src = reinterpret_cast<const float4*>(upartial + (static_cast<long>(q) * T + t) * D + d0);
+    const float4 lo = src[0], hi = src[1];
+    u[0] += lo.x; u[1] += lo.y; u[2] += lo.z; u[3] += lo.w;
+    u[4] += hi.x; u[5] += hi.y; u[6] += hi.z; u[7] += hi.w;
+  }
+  uint32_t pk[3][4];
+#pragma unroll
+  for (int j = 0; j < 8; j += 2) {
+    float v[2], p1[2], p2[2], p3[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      v[i] = u[j + i] / (1.f + expf(-u[j + i]));
+      p1[i] = bf16_to_f32(f32_to_bf16(v[i]));
+      const float r1 = v[i] - p1[i];          // exact
+      p2[i] = bf16_to_f32(f32_to_bf16(r1));
+      p3[i] = r1 - p2[i];                     // exact; rounded to bf16 by the pack below
+    }
+    pk[0][j / 2] = pack_bf16x2(p1[0], p1[1]);
+    pk[1][j / 2] = pack_bf16x2(p2[0], p2[1]);
+    pk[2][j / 2] = pack_bf16x2(p3[0], p3[1]);
+  }
+  bf16_t* row = a_planes + static_cast<long>(t) * 3 * D + d0;
+#pragma unroll
+  for (int p = 0; p < 3; ++p) {
+    u32x4 v = {pk[p][0], pk[p][1], pk[p][2], pk[p][3]};
+    *reinterpret_cast<u32x4*>(row + p * D) = v;
+  }
+}
 
-template <int TOK>
-__global__ __launch_bounds__(256) void predictor_residual_kernel(const float* __restrict__ upartial, int KS2,
-                                                                 const float* __restrict__ w2_hat, int T,
-                                                                 int D, int E, float* __restrict__ r_plane) {
-  constexpr int TPT = TOK / 4;           // tokens per thread
-  extern __shared__ float4 s_lds4[];
-  float* s_silu = reinterpret_cast<float*>(s_lds4);   // [TOK][D]
-  float* s_w2 = s_silu + TOK * D;                     // [256][kResidStride]
-  const int tid = threadIdx.x, lane = tid & 63, tg = tid >> 6;
-  const int t0 = blockIdx.x * TOK;
-  // u = sum of the split-K partials, sixteen elements per thread at a time so that the loads of a
-  // round are all in flight together; the TOK rows of a partial are contiguous ([t0 .. t0+TOK) x D)
-  const int n_valid = min(TOK, T - t0) * D;
-  for (int base = tid; base < TOK * D; base += 256 * 16) {
-    float u[16];
-#pragma unroll
-    for (int j = 0; j < 16; ++j) u[j] = 0.f;
-    for (int q = 0; q < KS2; ++q) {
-      const float* src = upartial + (static_cast<long>(q) * T + t0) * D;
-#pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        const int idx = base + 256 * j;
-        if (idx < n_valid) u[j] += src[idx];
-      }
-    }
-#pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      const int idx = base + 256 * j;
-      if (idx < TOK * D) s_silu[idx] = (idx < n_valid) ? u[j] / (1.f + expf(-u[j])) : 0.f;
-    }
-  }
-  float acc[4][TPT];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int t = 0; t < TPT; ++t) acc[i][t] = 0.f;
-  const float* srow = s_silu + tg * TPT * D;
-  // slice of w2_hat: 256 rows x 16 columns; thread i holds float4 number i % 4 of rows i / 4, i / 4 + 64, ...
-  // (D % 8 == 0, so a float4 is inside the row or entirely past it).  The next slice is fetched into
-  // registers while the current one is consumed from LDS.
-  float4 wreg[4];
-  auto fetch = [&](int d0) {
-#pragma unroll
-    for (int pass = 0; pass < 4; ++pass) {
-      const int e = pass * 64 + (tid >> 2), c = (tid & 3) * 4;
-      wreg[pass] = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (e < E && d0 + c < D) wreg[pass] = *reinterpret_cast<const float4*>(w2_hat + static_cast<long>(e) * D + d0 + c);
-    }
-  };
-  fetch(0);
-  for (int d0 = 0; d0 < D; d0 += kResidSlice) {
-    __syncthreads();  // s_silu is complete / the previous slice has been consumed
-#pragma unroll
-    for (int pass = 0; pass < 4; ++pass)
-      *reinterpret_cast<float4*>(s_w2 + (pass * 64 + (tid >> 2)) * kResidStride + (tid & 3) * 4) = wreg[pass];
-    __syncthreads();
-    if (d0 + kResidSlice < D) fetch(d0 + kResidSlice);
-#pragma unroll
-    for (int c4 = 0; c4 < kResidSlice / 4; ++c4) {
-      if (d0 + 4 * c4 < D) {
-        float4 sv[TPT], wv[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) wv[i] = *reinterpret_cast<const float4*>(s_w2 + (lane + 64 * i) * kResidStride + 4 * c4);
-#pragma unroll
-        for (int t = 0; t < TPT; ++t) sv[t] = *reinterpret_cast<const float4*>(srow + t * D + d0 + 4 * c4);
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int t = 0; t < TPT; ++t) {
-            acc[i][t] = fmaf(wv[i].x, sv[t].x, acc[i][t]);
-            acc[i][t] = fmaf(wv[i].y, sv[t].y, acc[i][t]);
-            acc[i][t] = fmaf(wv[i].z, sv[t].z, acc[i][t]);
-            acc[i][t] = fmaf(wv[i].w, sv[t].w, acc[i][t]);
-          }
-      }
-    }
-  }
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int e = lane + 64 * i;
-#pragma unroll
-    for (int t = 0; t < TPT; ++t) {
-      const int tok = t0 + tg * TPT + t;
-      if (e < E && tok < T) r_plane[static_cast<long>(tok) * E + e] = acc[i][t];
-    }
-  }
+__global__ __launch_bounds__(256) void resid_w2_split_kernel(const float* __restrict__ w2_hat, int E, int D,
+                                                             bf16_t* __restrict__ b_planes) {
+  const long gid = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (gid >= static_cast<long>(E) * D) return;
+  const int e = static_cast<int>(gid / D), d = static_cast<int>(gid % D);
+  const float v = w2_hat[gid];
+  const bf16_t hi = f32_to_bf16(v);
+  const float r1 = v - bf16_to_f32(hi);
+  const bf16_t mid = f32_to_bf16(r1);
+  const bf16_t lo = f32_to_bf16(r1 - bf16_to_f32(mid));
+  const long plane = static_cast<long>(E) * 3 * D;
+  bf16_t* row = b_planes + static_cast<long>(e) * 3 * D + d;
+  row[0] = hi;          row[D] = hi;            row[2 * D] = hi;
+  row[plane] = mid;     row[plane + D] = mid;   row[plane + 2 * D] = 0;
+  row[2 * plane] = lo;  row[2 * plane + D] = 0; row[2 * plane + 2 * D] = 0;
 }
 
 struct RouteShape {
@@ -566,7 +534,7 @@ struct RouteShape {
 
 constexpr int kMaxSplitK = 16;
 
-static RouteShape route_shape(int T, int H, int E) {
+static RouteShape route_shape(int T, int H, int E, int max_split = kMaxSplitK) {
   RouteShape s;
   // 256-token tiles when a split of 8 or less still gives every CU a workgroup; they aim at one
   // workgroup per CU (fewer, longer K ranges and half the partial sums), 128-token tiles at two
@@ -579,7 +547,7 @@ static RouteShape route_shape(int T, int H, int E) {
   const int target = s.bm == 256 ? 256 : 512;
   int want = tiles > 0 ? (target + tiles - 1) / tiles : 1;
   if (want < 1) want = 1;
-  if (want > kMaxSplitK) want = kMaxSplitK;  // the softmax kernel adds the slices one after another
+  if (want > max_split) want = max_split;  // the softmax kernel adds the slices one after another
   if (want > ksteps) want = ksteps;
   int steps_per = (ksteps + want - 1) / want;
   s.k_chunk = steps_per * GBK;
@@ -609,21 +577,26 @@ static void launch_gate_gemm(const RouteShape& sh, hipStream_t st, const bf16_t*
 
 // Workspace of a call: gate planes | logit partials (+ one plane for the residual) | u partials
 struct RouteLayout {
-  RouteShape gate, resid;
-  size_t partial_bytes, upartial_bytes, total;
+  RouteShape gate, resid, resid2;  // gate GEMM; u = W1_hat h; r = W2_hat silu(u)
+  size_t partial_bytes, upartial_bytes, a_bytes, b_bytes, total;
 };
 
 static RouteLayout route_layout(int T, int H, int E, int D) {
   RouteLayout L;
   L.gate = route_shape(T, H, E);
   const size_t plane = static_cast<size_t>(T > 0 ? T : 1) * E * sizeof(float);
-  L.partial_bytes = align_up((L.gate.ks + (D > 0 ? 1 : 0)) * plane, 256);
-  L.upartial_bytes = 0;
+  L.upartial_bytes = L.a_bytes = L.b_bytes = 0;
+  int extra = 0;
   if (D > 0) {
     L.resid = route_shape(T, H, D);
+    L.resid2 = route_shape(T, 3 * D, E, 4);  // few slices: the softmax kernel reads every one of them
     L.upartial_bytes = L.resid.partial_bytes;
+    L.a_bytes = align_up(static_cast<size_t>(T > 0 ? T : 1) * 3 * D * sizeof(bf16_t), 256);
+    L.b_bytes = L.resid2.planes_bytes;
+    extra = L.resid2.ks;
   }
-  L.total = L.gate.planes_bytes + L.partial_bytes + L.upartial_bytes;
+  L.partial_bytes = align_up((L.gate.ks + extra) * plane, 256);
+  L.total = L.gate.planes_bytes + L.partial_bytes + L.upartial_bytes + L.a_bytes + L.b_bytes;
   return L;
 }
 
@@ -657,7 +630,7 @@ static int route_impl(const char* name, const void* x_bf16, const float* w_gate,
   const RouteShape& sh = L.gate;
   PROBE_REQUIRE(workspace && aligned16(workspace) && workspace_bytes >= L.total, PROBE_EWORKSPACE,
                 "%s: workspace too small or misaligned (%zu < %zu)", name, workspace_bytes, L.total);
-  if (T > 0 && (sh.dma || (resid && L.resid.dma))) {
+  if (T > 0 && (sh.dma || (resid && (L.resid.dma || L.resid2.dma)))) {
     int rc = gate_prepare();
     if (rc != PROBE_OK) return rc;
   }
@@ -675,22 +648,19 @@ static int route_impl(const char* name, const void* x_bf16, const float* w_gate,
     launch_gate_gemm<3>(sh, st, x, planes, T, H, E, partial);
     int planes_to_sum = sh.ks;
     if (resid) {
-      // u = W1_hat h (one bf16 plane), then r = W2_hat silu(u) as one more plane of the logits
+      // u = W1_hat h (one bf16 plane); s = silu(u) and W2_hat split into planes; r = W2_hat s as
+      // further slices of the logits
+      char* base = static_cast<char*>(workspace) + sh.planes_bytes + L.partial_bytes + L.upartial_bytes;
+      bf16_t* a_planes = reinterpret_cast<bf16_t*>(base);
+      bf16_t* b_planes = reinterpret_cast<bf16_t*>(base + L.a_bytes);
       launch_gate_gemm<1>(L.resid, st, x, static_cast<const bf16_t*>(w1_hat), T, H, D, upartial);
-      float* r_plane = partial + static_cast<size_t>(sh.ks) * T * E;
-#define PROBE_RESID_LAUNCH(TOK)                                                                             \
-  hipLaunchKernelGGL(predictor_residual_kernel<TOK>, dim3((T + TOK - 1) / TOK), dim3(256),                  \
-                     (TOK * D + 256 * kResidStride) * sizeof(float), st, upartial, L.resid.ks, w2_hat,       \
-                     T, D, E, r_plane)
-      if (D <= 256 && T >= 32 * 512) {  // enough tokens for two workgroups per CU at 32 tokens each
-        PROBE_RESID_LAUNCH(32);
-      } else if (D <= 512) {
-        PROBE_RESID_LAUNCH(16);
-      } else {
-        PROBE_RESID_LAUNCH(8);
-      }
-#undef PROBE_RESID_LAUNCH
-      planes_to_sum = sh.ks + 1;
+      const long n_a = static_cast<long>(T) * (D / 8), n_b = static_cast<long>(E) * D;
+      hipLaunchKernelGGL(resid_silu_split_kernel, dim3(static_cast<unsigned>((n_a + 255) / 256)), dim3(256), 0, st,
+                         upartial, L.resid.ks, T, D, a_planes);
+      hipLaunchKernelGGL(resid_w2_split_kernel, dim3(static_cast<unsigned>((n_b + 255) / 256)), dim3(256), 0, st,
+                         w2_hat, E, D, b_planes);
+      launch_gate_gemm<3>(L.resid2, st, a_planes, b_planes, T, 3 * D, E, partial + static_cast<size_t>(sh.ks) * T * E);
+      planes_to_sum = sh.ks + L.resid2.ks;
     }
     int grid = (T + 31) / 32;
     if (grid > 4096) grid = 4096;
