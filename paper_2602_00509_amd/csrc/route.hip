@@ -14,6 +14,15 @@
 //               otherwise a register-staged kernel that zero-fills the K tail
 //   3. softmax  sixteen lanes per token: sum the KS partials in fixed order, add the bias,
 //               softmax over E, k rounds of row arg-max (ties to the lower index), weights, counts
+//
+// The predictor's residual MLP (Eq. 7) adds W2_hat silu(W1_hat h) to the logits before step 3:
+//   a. the same GEMM with one bf16 plane of W1_hat (D rows in place of experts) -> u partials
+//   b. sum of the u partials, SiLU in fp32, split of s = silu(u) into three bf16 planes laid side
+//      by side along K: A' = [s_hi | s_mid | s_lo], [T][3D]
+//   c. W2_hat split into planes arranged as B' = {[hi hi hi], [mid mid 0], [lo 0 0]}, [3][E][3D],
+//      so that step 2's three-plane GEMM over K = 3D forms the six largest of the nine plane
+//      products (what is dropped is below 2^-24 of the result)
+//   d. that GEMM; its split-K slices are written behind the gate's own, and step 3 sums them all
 #include <limits.h>
 
 #include <mutex>
