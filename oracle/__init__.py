@@ -1,4 +1,4 @@
-"""ctypes front end of the CPU oracle (``probe_oracle.c``, ``planner_oracle.c``).
+"""ctypes front end of the CPU oracle (``probe_oracle.c``, ``planner_oracle.c``, ``gating_oracle.c``).
 
 TEST INFRASTRUCTURE ONLY: the tests, ``__graft_entry__.smoke()`` and the ``cpu_baseline``
 leg of ``bench.py`` may import this package; the product path never does.  It imports
@@ -17,7 +17,7 @@ import threading
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRCS = [os.path.join(_HERE, "probe_oracle.c"), os.path.join(_HERE, "planner_oracle.c")]
+_SRCS = [os.path.join(_HERE, f) for f in ("probe_oracle.c", "planner_oracle.c", "gating_oracle.c")]
 _LIB = os.path.join(_HERE, "libprobe_oracle.so")
 _lock = threading.Lock()
 _lib = None
@@ -122,6 +122,43 @@ def predict_topk_residual(h_prev_bits, w_gate_next, bias_next, tokens_per_group,
         # a = (x, w_gate, bias, G, tpg, T, H, E, k, renorm, outputs...): insert the residual after tpg
         return fn(*a[:5], _p(w1_hat_bits, C.c_uint16), _p(w2_hat, C.c_float), D, *a[5:])
     return _route(bound, h_prev_bits, w_gate_next, bias_next, tokens_per_group, k, renormalize)
+
+
+def route_grouped(x_bits, w_gate, bias=None, tokens_per_group=None, select_bias=None, scoring="sigmoid",
+                  n_group=1, topk_group=1, group_top=2, k=2, renormalize=True, routed_scale=1.0):
+    """Group-limited gate (``gating_oracle.c``): scores, selection scores, group scores, allowed
+    groups, chosen experts, gating values, counts; all floating point in fp64."""
+    x_bits = _chk(x_bits, np.uint16)
+    T, H = x_bits.shape
+    w_gate = _chk(w_gate, np.float32)
+    E = w_gate.shape[0]
+    assert w_gate.shape == (E, H)
+    if bias is not None:
+        bias = _chk(bias, np.float32)
+        if bias.ndim == 1:
+            bias = bias.reshape(1, E)
+        G = bias.shape[0]
+        assert bias.shape == (G, E)
+    else:
+        G = 1
+    if select_bias is not None:
+        select_bias = _chk(select_bias, np.float32, (E,))
+    tpg = int(tokens_per_group) if tokens_per_group else max(T, 1)
+    mode = {"softmax": 0, "sigmoid": 1}[scoring]
+    out = dict(logits=np.empty((T, E)), scores=np.empty((T, E)), choice=np.empty((T, E)),
+               group_scores=np.empty((T, n_group)), groups=np.empty((T, topk_group), np.int32),
+               idx=np.empty((T, k), np.int32), w=np.empty((T, k)), counts=np.empty((E,), np.int32))
+    fn = _load().oracle_route_grouped
+    fn.argtypes = None
+    rc = fn(_p(x_bits, C.c_uint16), _p(w_gate, C.c_float), _p(bias, C.c_float), G, tpg,
+            _p(select_bias, C.c_float), mode, int(n_group), int(topk_group), int(group_top),
+            int(bool(renormalize)), C.c_double(float(routed_scale)), T, H, E, int(k),
+            _p(out["logits"], C.c_double), _p(out["scores"], C.c_double), _p(out["choice"], C.c_double),
+            _p(out["group_scores"], C.c_double), _p(out["groups"], C.c_int32), _p(out["idx"], C.c_int32),
+            _p(out["w"], C.c_double), _p(out["counts"], C.c_int32))
+    if rc != 0:
+        raise ValueError("oracle route_grouped failed: %d" % rc)
+    return out
 
 
 def permute(topk_idx, rep_off, rep_slot, rep_weight, num_slots, x_bits=None):
