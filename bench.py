@@ -306,6 +306,29 @@ def main():
                              "params": kw, "moves": st[3], "bottleneck_latency_before": st[0],
                              "bottleneck_latency_after": st[1]}
 
+    # the group-limited gate (sigmoid scores, E / 32 groups of 32 experts, half of them allowed) on the same
+    # inputs, timed on its own next to the plain router; not part of `value`
+    if E % 32 == 0 and E >= 64:
+        ng = E // 32
+        gkw = dict(scoring="sigmoid", n_group=ng, topk_group=max(ng // 2, 1), group_top=2, k=k, renormalize=True,
+                   routed_scale=2.5)
+        d_sb = torch.zeros((E,), dtype=torch.float32, device=dev)
+        times = {}
+        for name, fn in (("route_topk", lambda: probe.route_topk(d_xs[0], d_wg, d_bias[0], tpg, k, True, workspace=ws_route)),
+                         ("route_grouped", lambda: probe.route_grouped(d_xs[0], d_wg, d_bias[0], tpg, d_sb, workspace=ws_route, **gkw))):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(20):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            times[name] = e0.elapsed_time(e1) * 1e3 / 20
+        result["grouped_gate"] = {"us_per_call": times["route_grouped"], "plain_router_us_per_call": times["route_topk"],
+                                  "n_group": ng, "topk_group": gkw["topk_group"], "scoring": "sigmoid"}
+
     if args.calibrate_copy:
         src = torch.ones((1 << 28,), dtype=torch.float32, device=dev)      # 1 GiB
         dst = torch.empty_like(src)

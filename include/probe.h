@@ -59,6 +59,7 @@ extern "C" {
 #define PROBE_MAX_TOPK      8  /* k                         */
 #define PROBE_MAX_SLOTS  1024  /* S                         */
 #define PROBE_MAX_RESIDUAL_WIDTH 1024 /* D of the predictor's residual MLP */
+#define PROBE_MAX_GROUPS   16  /* n_group of the group-limited gate */
 
 /* Text of the last error raised on the calling thread ("" if none). Host pointer, owned by
  * the library, valid until the next failing call on the same thread. */
@@ -97,6 +98,48 @@ int probe_route_topk(const void* x_bf16, const float* w_gate, const float* bias,
                      int renormalize, int32_t* topk_idx, float* topk_w, float* probs,
                      int32_t* expert_counts, void* workspace, size_t workspace_bytes,
                      void* stream);
+
+/* The router with the gate of a model that limits a token to a few groups of experts.  The paper
+ * (Sec. 1) targets such models and leaves each model's gate as published; this is the gate of the
+ * DeepSeek-V3 technical report (Sec. 2.1.2: sigmoid affinities, gating values normalised over the
+ * chosen experts, a balancing bias that enters the selection only) with its node-limited routing in
+ * the form the released model configures.  Per token:
+ *   l_e = logits as in probe_route_topk (bias is the paper's b_L, added to the logits)
+ *   s_e = sigmoid(l_e) (PROBE_SCORE_SIGMOID) or softmax(l)_e (PROBE_SCORE_SOFTMAX)
+ *   c_e = s_e + select_bias[e]                      selection score (select_bias may be NULL)
+ *   group j = experts j*E/n_group .. (j+1)*E/n_group - 1; its score is the sum of its group_top
+ *             largest c_e; the topk_group groups with the largest scores are allowed
+ *   topk_idx = the k allowed experts with the largest c_e, descending
+ *   topk_w   = s_e of the chosen experts (without select_bias), divided by their sum when
+ *              renormalize is non-zero, times routed_scale
+ * Equal scores go to the lower index (groups and experts alike).  n_group = topk_group = 1 with
+ * softmax scores is probe_route_topk.  All decisions are taken in fp32.
+ *   select_bias    device, fp32 [E] or NULL
+ *   gating         host pointer, read during the call
+ *   scores         device, fp32 [T,E] or NULL (out, s_e)
+ * Other arguments, workspace, arithmetic of the logits and limits as probe_route_topk; in addition
+ * n_group <= 16 and divides E, 1 <= topk_group <= n_group, 1 <= group_top <= E / n_group,
+ * k <= topk_group * E / n_group.
+ */
+#define PROBE_SCORE_SOFTMAX 0
+#define PROBE_SCORE_SIGMOID 1
+
+typedef struct probe_gating {
+  int32_t scoring;     /* PROBE_SCORE_SOFTMAX or PROBE_SCORE_SIGMOID */
+  int32_t n_group;     /* groups of E / n_group consecutive experts */
+  int32_t topk_group;  /* groups a token may use */
+  int32_t group_top;   /* how many of a group's largest selection scores make up its score */
+  int32_t renormalize; /* divide the gating values by their sum */
+  float routed_scale;  /* factor on the gating values */
+} probe_gating;
+
+size_t probe_route_grouped_workspace_bytes(int T, int H, int E, int k);
+
+int probe_route_grouped(const void* x_bf16, const float* w_gate, const float* bias, int bias_groups,
+                        int tokens_per_group, const float* select_bias, const probe_gating* gating,
+                        int T, int H, int E, int k, int32_t* topk_idx, float* topk_w, float* scores,
+                        int32_t* expert_counts, void* workspace, size_t workspace_bytes,
+                        void* stream);
 
 /* Gate-initialised lookahead predictor (Eq. 7) with its trainable residual at the zero
  * initialisation the paper prescribes: the cloned router (w_gate_next, bias_next) of layer L

@@ -279,6 +279,79 @@ __device__ __forceinline__ int row_min_i(int v) {
   return v;
 }
 
+// Logit row pieces of U tokens: the KS split-K slices are added in ascending order, then the bias row
+// of the token's group.  Lane `sub` receives the experts 64*i + 4*sub + j; entries past E are zero.
+template <int NV, int U>
+__device__ __forceinline__ void load_logit_rows(const float* __restrict__ partial, int ld, int KS,
+                                                const float* __restrict__ bias, int G, int tpg, int T, int E,
+                                                bool vec, int sub, const int (&tt)[U], float (&l)[U][NV * 4]) {
+  constexpr int NL = NV * 4;
+  if (vec) {
+    float4 accv[U][NV];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int i = 0; i < NV; ++i) accv[u][i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int q0 = 0; q0 < KS; q0 += 2) {
+      // all loads of a round of two split-K slices (of both tokens) are issued before any is consumed
+      float4 tmp[2][U][NV];
+#pragma unroll
+      for (int r = 0; r < 2; ++r) {
+        const int q = min(q0 + r, KS - 1);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+          for (int i = 0; i < NV; ++i) {
+            const int e0 = min(64 * i + 4 * sub, E - 4);
+            tmp[r][u][i] = *reinterpret_cast<const float4*>(partial + (static_cast<long>(q) * T + tt[u]) * ld + e0);
+          }
+      }
+#pragma unroll
+      for (int r = 0; r < 2; ++r)
+        if (q0 + r < KS) {
+#pragma unroll
+          for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+              accv[u][i].x += tmp[r][u][i].x; accv[u][i].y += tmp[r][u][i].y;
+              accv[u][i].z += tmp[r][u][i].z; accv[u][i].w += tmp[r][u][i].w;
+            }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      int g = 0;
+      if (bias) g = min(tt[u] / tpg, G - 1);
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        const int e0 = 64 * i + 4 * sub;
+        float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (bias && e0 < E) bv = *reinterpret_cast<const float4*>(bias + static_cast<long>(g) * E + e0);
+        l[u][4 * i] = accv[u][i].x + bv.x;
+        l[u][4 * i + 1] = accv[u][i].y + bv.y;
+        l[u][4 * i + 2] = accv[u][i].z + bv.z;
+        l[u][4 * i + 3] = accv[u][i].w + bv.w;
+      }
+    }
+  } else {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      int g = 0;
+      if (bias) g = min(tt[u] / tpg, G - 1);
+#pragma unroll
+      for (int i = 0; i < NL; ++i) {
+        const int e = 64 * (i >> 2) + 4 * sub + (i & 3);
+        float sacc = 0.f;
+        if (e < E) {
+          for (int q = 0; q < KS; ++q) sacc += partial[(static_cast<long>(q) * T + tt[u]) * ld + e];
+          if (bias) sacc += bias[static_cast<long>(g) * E + e];
+        }
+        l[u][i] = sacc;
+      }
+    }
+  }
+}
+
 // Two tokens per row are in flight (U = 2) so that the dependent DPP chains of one overlap the
 // other's.  A chosen logit is overwritten with -inf; incoming logits are clamped to >= -FLT_MAX
 // (NaN too), so -inf only ever means "taken".  The weight of a winner is recomputed from its
@@ -308,70 +381,7 @@ __global__ __launch_bounds__(256) void gate_softmax_topk_kernel(
       live[u] = t0 + 4 * u < T;
       tt[u] = live[u] ? t0 + 4 * u : t0;
     }
-    if (vec) {
-      float4 accv[U][NV];
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-#pragma unroll
-        for (int i = 0; i < NV; ++i) accv[u][i] = make_float4(0.f, 0.f, 0.f, 0.f);
-      for (int q0 = 0; q0 < KS; q0 += 2) {
-        // all loads of a round of two split-K slices (of both tokens) are issued before any is consumed
-        float4 tmp[2][U][NV];
-#pragma unroll
-        for (int r = 0; r < 2; ++r) {
-          const int q = min(q0 + r, KS - 1);
-#pragma unroll
-          for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int i = 0; i < NV; ++i) {
-              const int e0 = min(64 * i + 4 * sub, E - 4);
-              tmp[r][u][i] = *reinterpret_cast<const float4*>(partial + (static_cast<long>(q) * T + tt[u]) * ld + e0);
-            }
-        }
-#pragma unroll
-        for (int r = 0; r < 2; ++r)
-          if (q0 + r < KS) {
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-              for (int i = 0; i < NV; ++i) {
-                accv[u][i].x += tmp[r][u][i].x; accv[u][i].y += tmp[r][u][i].y;
-                accv[u][i].z += tmp[r][u][i].z; accv[u][i].w += tmp[r][u][i].w;
-              }
-          }
-      }
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        int g = 0;
-        if (bias) g = min(tt[u] / tpg, G - 1);
-#pragma unroll
-        for (int i = 0; i < NV; ++i) {
-          const int e0 = 64 * i + 4 * sub;
-          float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
-          if (bias && e0 < E) bv = *reinterpret_cast<const float4*>(bias + static_cast<long>(g) * E + e0);
-          l[u][4 * i] = accv[u][i].x + bv.x;
-          l[u][4 * i + 1] = accv[u][i].y + bv.y;
-          l[u][4 * i + 2] = accv[u][i].z + bv.z;
-          l[u][4 * i + 3] = accv[u][i].w + bv.w;
-        }
-      }
-    } else {
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        int g = 0;
-        if (bias) g = min(tt[u] / tpg, G - 1);
-#pragma unroll
-        for (int i = 0; i < NL; ++i) {
-          const int e = 64 * (i >> 2) + 4 * sub + (i & 3);
-          float sacc = 0.f;
-          if (e < E) {
-            for (int q = 0; q < KS; ++q) sacc += partial[(static_cast<long>(q) * T + tt[u]) * ld + e];
-            if (bias) sacc += bias[static_cast<long>(g) * E + e];
-          }
-          l[u][i] = sacc;
-        }
-      }
-    }
+    load_logit_rows<NV, U>(partial, ld, KS, bias, G, tpg, T, E, vec, sub, tt, l);
     float mx[U], inv[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -455,6 +465,242 @@ __global__ __launch_bounds__(256) void gate_softmax_topk_kernel(
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       if (renorm) wsel[u] /= wtot[u];
+      if (live[u] && sub < k) {
+        const long t = t0 + 4 * u;
+        topk_idx[t * k + sub] = isel[u];
+        topk_w[t * k + sub] = wsel[u];
+        if (counts) atomicAdd(&hist[isel[u]], 1);
+      }
+    }
+  }
+  __syncthreads();
+  if (counts && tid < E && hist[tid] != 0) atomicAdd(&counts[tid], hist[tid]);
+}
+
+// (m1, m2) = the two largest of this lane's pair and the pair N lanes away in the row
+template <int N>
+__device__ __forceinline__ void top2_merge(float& m1, float& m2) {
+  const float o1 = dpp_ror<N>(m1), o2 = dpp_ror<N>(m2);
+  m2 = fmaxf(fminf(m1, o1), fmaxf(m2, o2));
+  m1 = fmaxf(m1, o1);
+}
+
+// ---- 3b. group-limited gate -----------------------------------------------------------------
+// Same lane layout and logit loading as above.  Per token: scores s (sigmoid of each logit, or the
+// softmax), selection scores c = s + select_bias, a score per group of E / n_group consecutive
+// experts (sum of its group_top largest c), the topk_group best groups, the k largest c among their
+// experts, gating values from s.  Every decision is an arg-max over a DPP row with ties to the
+// lower index, so all sixteen lanes of a token agree bit for bit.  Lane j keeps the score of group
+// j (n_group <= 16); sets of groups and of consumed entries are bit masks.
+template <int NV>
+__global__ __launch_bounds__(256) void gate_grouped_topk_kernel(
+    const float* __restrict__ partial, int ld, int KS, const float* __restrict__ bias, int G, int tpg,
+    const float* __restrict__ select_bias, int T, int E, int k, int scoring, int n_group, int topk_group,
+    int group_top, int renorm, float routed_scale, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+    float* __restrict__ scores, int32_t* __restrict__ counts) {
+  constexpr int U = 2, NL = NV * 4;
+  __shared__ int32_t hist[PROBE_MAX_EXPERTS];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int sub = lane & 15, grp = lane >> 4;
+  hist[tid] = 0;
+  __syncthreads();
+  const float ninf = -__builtin_inff(), fmin_ = -3.402823466e38f;
+  const bool vec = (E & 3) == 0 && (ld & 3) == 0;
+  const int gs = E / n_group;
+  int gid[NL];      // group of entry i, -1 past E
+  float sb[NL];
+#pragma unroll
+  for (int i = 0; i < NL; ++i) {
+    const int e = 64 * (i >> 2) + 4 * sub + (i & 3);
+    gid[i] = e < E ? e / gs : -1;
+    sb[i] = (select_bias && e < E) ? select_bias[e] : 0.f;
+  }
+  const int tokens_per_pass = gridDim.x * 16 * U;
+  for (int t0 = ((blockIdx.x * 4 + wv) * U) * 4 + grp; t0 < T; t0 += tokens_per_pass) {
+    int tt[U];
+    bool live[U];
+    float sc[U][NL], c[U][NL];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      live[u] = t0 + 4 * u < T;
+      tt[u] = live[u] ? t0 + 4 * u : t0;
+    }
+    load_logit_rows<NV, U>(partial, ld, KS, bias, G, tpg, T, E, vec, sub, tt, sc);
+    // scores (in place of the logits) and selection scores
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+      for (int i = 0; i < NL; ++i) {
+        float v = sc[u][i];
+        v = (v >= fmin_) ? v : fmin_;  // NaN and -inf become the most negative finite value
+        sc[u][i] = (gid[i] >= 0) ? v : ninf;
+      }
+      if (scoring == 1) {
+#pragma unroll
+        for (int i = 0; i < NL; ++i) sc[u][i] = 1.f / (1.f + expf(-sc[u][i]));  // 0 past E
+      } else {
+        float m = sc[u][0];
+#pragma unroll
+        for (int i = 1; i < NL; ++i) m = fmaxf(m, sc[u][i]);
+        m = row_max(m);
+        float sum = 0.f;
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+          sc[u][i] = expf(sc[u][i] - m);
+          sum += sc[u][i];
+        }
+        const float inv = 1.f / row_sum(sum);
+#pragma unroll
+        for (int i = 0; i < NL; ++i) sc[u][i] *= inv;
+      }
+#pragma unroll
+      for (int i = 0; i < NL; ++i) {
+        float v = sc[u][i] + sb[i];
+        v = (v >= fmin_) ? v : fmin_;
+        c[u][i] = (gid[i] >= 0) ? v : ninf;
+      }
+      if (scores && live[u]) {
+        const long t = t0 + 4 * u;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+          const int e0 = 64 * i + 4 * sub;
+          if (vec) {
+            if (e0 < E)
+              *reinterpret_cast<float4*>(scores + t * E + e0) =
+                  make_float4(sc[u][4 * i], sc[u][4 * i + 1], sc[u][4 * i + 2], sc[u][4 * i + 3]);
+          } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+              if (e0 + j < E) scores[t * E + e0 + j] = sc[u][4 * i + j];
+          }
+        }
+      }
+    }
+    // group scores.  Only the VALUES of a group's largest selection scores matter, so for
+    // group_top <= 2 a (largest, second) pair is merged across the row with max / min, which is
+    // exact and order-free; otherwise group_top rounds of arg-max inside the group.
+    float gscore[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) gscore[u] = ninf;
+    if (group_top <= 2) {
+      for (int j = 0; j < n_group; ++j) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          float m1 = ninf, m2 = ninf;
+#pragma unroll
+          for (int i = 0; i < NL; ++i) {
+            const float v = (gid[i] == j) ? c[u][i] : ninf;
+            m2 = fmaxf(m2, fminf(m1, v));
+            m1 = fmaxf(m1, v);
+          }
+          top2_merge<8>(m1, m2);
+          top2_merge<4>(m1, m2);
+          top2_merge<2>(m1, m2);
+          top2_merge<1>(m1, m2);
+          const float sum = (group_top == 2) ? m1 + m2 : m1;
+          gscore[u] = (sub == j) ? sum : gscore[u];
+        }
+      }
+    } else {
+      unsigned used[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) used[u] = 0u;
+      for (int j = 0; j < n_group; ++j) {
+        float sum[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) sum[u] = 0.f;
+        for (int r = 0; r < group_top; ++r) {
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            float m = ninf;
+#pragma unroll
+            for (int i = 0; i < NL; ++i) {
+              const bool open = gid[i] == j && !((used[u] >> i) & 1u);
+              m = open ? fmaxf(m, c[u][i]) : m;
+            }
+            const float best = row_max(m);
+            int cand = INT_MAX;
+#pragma unroll
+            for (int i = NL - 1; i >= 0; --i) {
+              const int e = 64 * (i >> 2) + 4 * sub + (i & 3);
+              const bool open = gid[i] == j && !((used[u] >> i) & 1u);
+              cand = (open && c[u][i] == best) ? e : cand;
+            }
+            const int be = row_min_i(cand);
+#pragma unroll
+            for (int i = 0; i < NL; ++i) {
+              const int e = 64 * (i >> 2) + 4 * sub + (i & 3);
+              used[u] |= (e == be) ? (1u << i) : 0u;
+            }
+            sum[u] += best;
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) gscore[u] = (sub == j) ? sum[u] : gscore[u];
+      }
+    }
+    // allowed groups
+    unsigned allowed[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) allowed[u] = 0u;
+    for (int r = 0; r < topk_group; ++r) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const bool open = sub < n_group && !((allowed[u] >> sub) & 1u);
+        const float best = row_max(open ? gscore[u] : ninf);
+        const int bg = row_min_i((open && gscore[u] == best) ? sub : INT_MAX);
+        allowed[u] |= 1u << (bg & 15);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int i = 0; i < NL; ++i) {
+        const bool ok = gid[i] >= 0 && ((allowed[u] >> (gid[i] & 15)) & 1u);
+        c[u][i] = ok ? c[u][i] : ninf;
+      }
+    // k largest selection scores among the allowed experts; -inf now means "not available"
+    int isel[U];
+    float wsel[U], wtot[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      isel[u] = 0;
+      wsel[u] = 0.f;
+      wtot[u] = 0.f;
+    }
+    for (int s = 0; s < k; ++s) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        float m = c[u][0];
+#pragma unroll
+        for (int i = 1; i < NL; ++i) m = fmaxf(m, c[u][i]);
+        const float best = row_max(m);
+        int cand = INT_MAX;
+#pragma unroll
+        for (int i = NL - 1; i >= 0; --i) {
+          const int e = 64 * (i >> 2) + 4 * sub + (i & 3);
+          cand = (c[u][i] == best) ? e : cand;
+        }
+        const int be = row_min_i(cand);
+        float mine = ninf;  // the owner's score of the winner, without the selection bias
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+          const int e = 64 * (i >> 2) + 4 * sub + (i & 3);
+          mine = (e == be) ? sc[u][i] : mine;
+          c[u][i] = (e == be) ? ninf : c[u][i];
+        }
+        const float pw = row_max(mine);
+        wtot[u] += pw;
+        if (sub == s) {
+          isel[u] = be;
+          wsel[u] = pw;
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (renorm) wsel[u] /= wtot[u];
+      wsel[u] *= routed_scale;
       if (live[u] && sub < k) {
         const long t = t0 + 4 * u;
         topk_idx[t * k + sub] = isel[u];
@@ -615,7 +861,7 @@ static int route_impl(const char* name, const void* x_bf16, const float* w_gate,
                       int bias_groups, int tokens_per_group, const void* w1_hat, const float* w2_hat, int D,
                       int T, int H, int E, int k, int renormalize, int32_t* topk_idx, float* topk_w,
                       float* probs, int32_t* expert_counts, void* workspace, size_t workspace_bytes,
-                      void* stream) {
+                      void* stream, const probe_gating* gating = nullptr, const float* select_bias = nullptr) {
   PROBE_REQUIRE(T >= 0 && H > 0 && E > 0 && k > 0 && k <= E, PROBE_EINVAL,
                 "%s: bad dims T=%d H=%d E=%d k=%d", name, T, H, E, k);
   PROBE_REQUIRE(bias == nullptr || (bias_groups >= 1 && tokens_per_group >= 1), PROBE_EINVAL,
@@ -623,6 +869,20 @@ static int route_impl(const char* name, const void* x_bf16, const float* w_gate,
   PROBE_REQUIRE(E <= PROBE_MAX_EXPERTS && k <= PROBE_MAX_TOPK && H % 8 == 0, PROBE_EUNSUPPORTED,
                 "%s: needs E <= %d, k <= %d, H %% 8 == 0 (E=%d k=%d H=%d)", name, PROBE_MAX_EXPERTS,
                 PROBE_MAX_TOPK, E, k, H);
+  if (gating) {
+    const probe_gating& g = *gating;
+    PROBE_REQUIRE(g.scoring == PROBE_SCORE_SOFTMAX || g.scoring == PROBE_SCORE_SIGMOID, PROBE_EINVAL,
+                  "%s: scoring=%d", name, g.scoring);
+    PROBE_REQUIRE(g.n_group >= 1 && E % g.n_group == 0 && g.topk_group >= 1 && g.topk_group <= g.n_group,
+                  PROBE_EINVAL, "%s: n_group=%d must divide E=%d, topk_group=%d must be in 1..n_group", name,
+                  g.n_group, E, g.topk_group);
+    PROBE_REQUIRE(g.group_top >= 1 && g.group_top <= E / g.n_group && k <= g.topk_group * (E / g.n_group),
+                  PROBE_EINVAL, "%s: group_top=%d and k=%d must fit %d groups of %d experts", name, g.group_top, k,
+                  g.topk_group, E / g.n_group);
+    PROBE_REQUIRE(g.n_group <= PROBE_MAX_GROUPS, PROBE_EUNSUPPORTED, "%s: needs n_group <= %d (n_group=%d)", name,
+                  PROBE_MAX_GROUPS, g.n_group);
+    PROBE_REQUIRE(aligned16(select_bias), PROBE_EALIGN, "%s: select_bias must be 16-byte aligned", name);
+  }
   PROBE_REQUIRE(w_gate != nullptr, PROBE_EINVAL, "%s: w_gate is NULL", name);
   PROBE_REQUIRE(T == 0 || (x_bf16 && topk_idx && topk_w), PROBE_EINVAL, "%s: null pointer", name);
   PROBE_REQUIRE(aligned16(x_bf16) && aligned16(w_gate), PROBE_EALIGN,
@@ -677,7 +937,20 @@ static int route_impl(const char* name, const void* x_bf16, const float* w_gate,
 #define PROBE_TOPK_LAUNCH(V)                                                                               \
   hipLaunchKernelGGL(gate_softmax_topk_kernel<V>, dim3(grid), dim3(256), 0, st, partial, E, planes_to_sum, bias, \
                      G, tpg, T, E, k, renormalize ? 1 : 0, topk_idx, topk_w, probs, expert_counts)
-    if (E <= 64) {
+#define PROBE_GROUPED_LAUNCH(V)                                                                              \
+  hipLaunchKernelGGL(gate_grouped_topk_kernel<V>, dim3(grid), dim3(256), 0, st, partial, E, planes_to_sum, bias, \
+                     G, tpg, select_bias, T, E, k, gating->scoring, gating->n_group, gating->topk_group,         \
+                     gating->group_top, gating->renormalize ? 1 : 0, gating->routed_scale, topk_idx, topk_w,     \
+                     probs, expert_counts)
+    if (gating) {
+      if (E <= 64) {
+        PROBE_GROUPED_LAUNCH(1);
+      } else if (E <= 128) {
+        PROBE_GROUPED_LAUNCH(2);
+      } else {
+        PROBE_GROUPED_LAUNCH(4);
+      }
+    } else if (E <= 64) {
       PROBE_TOPK_LAUNCH(1);
     } else if (E <= 128) {
       PROBE_TOPK_LAUNCH(2);
@@ -685,6 +958,7 @@ static int route_impl(const char* name, const void* x_bf16, const float* w_gate,
       PROBE_TOPK_LAUNCH(4);
     }
 #undef PROBE_TOPK_LAUNCH
+#undef PROBE_GROUPED_LAUNCH
   }
   return check_launch(name);
 }
@@ -783,6 +1057,22 @@ extern "C" int probe_route_topk(const void* x_bf16, const float* w_gate, const f
   return probe::route_impl("probe_route_topk", x_bf16, w_gate, bias, bias_groups, tokens_per_group, nullptr,
                            nullptr, 0, T, H, E, k, renormalize, topk_idx, topk_w, probs, expert_counts,
                            workspace, workspace_bytes, stream);
+}
+
+extern "C" size_t probe_route_grouped_workspace_bytes(int T, int H, int E, int k) {
+  return probe_route_topk_workspace_bytes(T, H, E, k);
+}
+
+// The router with a model's own gate: same GEMM, group-limited selection in place of the plain top-k.
+extern "C" int probe_route_grouped(const void* x_bf16, const float* w_gate, const float* bias, int bias_groups,
+                                   int tokens_per_group, const float* select_bias, const probe_gating* gating,
+                                   int T, int H, int E, int k, int32_t* topk_idx, float* topk_w, float* scores,
+                                   int32_t* expert_counts, void* workspace, size_t workspace_bytes,
+                                   void* stream) {
+  PROBE_REQUIRE(gating != nullptr, PROBE_EINVAL, "probe_route_grouped: gating is NULL");
+  return probe::route_impl("probe_route_grouped", x_bf16, w_gate, bias, bias_groups, tokens_per_group, nullptr,
+                           nullptr, 0, T, H, E, k, gating->renormalize, topk_idx, topk_w, scores, expert_counts,
+                           workspace, workspace_bytes, stream, gating, select_bias);
 }
 
 // Eq. 7 with the residual at its zero initialisation is the cloned router applied to the

@@ -72,6 +72,11 @@ def lib():
                                                [C.c_void_p] * 2 + [C.c_size_t, C.c_void_p])
         L.probe_grouped_ffn_gather.restype = C.c_int
         L.probe_combine.argtypes = [C.c_void_p] * 3 + [C.c_int] * 3 + [C.c_void_p] * 2
+        L.probe_route_grouped_workspace_bytes.restype = C.c_size_t
+        L.probe_route_grouped_workspace_bytes.argtypes = [C.c_int] * 4
+        L.probe_route_grouped.restype = C.c_int
+        L.probe_route_grouped.argtypes = ([C.c_void_p] * 3 + [C.c_int] * 2 + [C.c_void_p, C.POINTER(_Gating)] +
+                                          [C.c_int] * 4 + [C.c_void_p] * 5 + [C.c_size_t, C.c_void_p])
         L.probe_route_predict_topk_workspace_bytes.restype = C.c_size_t
         L.probe_route_predict_topk_workspace_bytes.argtypes = [C.c_int] * 4
         L.probe_route_predict_topk.restype = C.c_int
@@ -185,6 +190,53 @@ def route_topk(x, w_gate, bias=None, tokens_per_group=None, k=2, renormalize=Tru
     """probe_route_topk: returns dict(idx int32 [T,k], w fp32 [T,k], probs?, counts?)."""
     return _route(lib().probe_route_topk, x, w_gate, bias, tokens_per_group, k, renormalize,
                   want_probs, want_counts, out, workspace, stream)
+
+
+class _Gating(C.Structure):
+    _fields_ = [("scoring", C.c_int32), ("n_group", C.c_int32), ("topk_group", C.c_int32),
+                ("group_top", C.c_int32), ("renormalize", C.c_int32), ("routed_scale", C.c_float)]
+
+
+SCORE_SOFTMAX, SCORE_SIGMOID = 0, 1
+
+
+def route_grouped(x, w_gate, bias=None, tokens_per_group=None, select_bias=None, *, scoring="sigmoid",
+                  n_group=1, topk_group=1, group_top=2, k=2, renormalize=True, routed_scale=1.0,
+                  want_scores=False, want_counts=True, out=None, workspace=None, stream=None):
+    """probe_route_grouped: group-limited gate; returns dict(idx, w, scores?, counts?)."""
+    T, H = x.shape
+    E = w_gate.shape[0]
+    _want(x, torch.bfloat16, (T, H), "x")
+    _want(w_gate, torch.float32, (E, H), "w_gate")
+    G = 1
+    if bias is not None:
+        if bias.dim() == 1:
+            bias = bias.view(1, E)
+        G = bias.shape[0]
+        _want(bias, torch.float32, (G, E), "bias")
+    if select_bias is not None:
+        _want(select_bias, torch.float32, (E,), "select_bias")
+    tpg = int(tokens_per_group) if tokens_per_group else max(T, 1)
+    gating = _Gating({"softmax": SCORE_SOFTMAX, "sigmoid": SCORE_SIGMOID}[scoring], int(n_group), int(topk_group),
+                     int(group_top), int(bool(renormalize)), float(routed_scale))
+    out = dict(out) if out else {}
+    dev = x.device
+    out.setdefault("idx", torch.empty((T, k), dtype=torch.int32, device=dev))
+    out.setdefault("w", torch.empty((T, k), dtype=torch.float32, device=dev))
+    if want_scores:
+        out.setdefault("scores", torch.empty((T, E), dtype=torch.float32, device=dev))
+    if want_counts:
+        out.setdefault("counts", torch.empty((E,), dtype=torch.int32, device=dev))
+    _want(out["idx"], torch.int32, (T, k), "idx")
+    _want(out["w"], torch.float32, (T, k), "w")
+    workspace = _ws(workspace, int(lib().probe_route_grouped_workspace_bytes(T, H, E, k)), dev)
+    rc = lib().probe_route_grouped(_ptr(x), _ptr(w_gate), _ptr(bias), G, tpg, _ptr(select_bias), C.byref(gating),
+                                   T, H, E, k, _ptr(out["idx"]), _ptr(out["w"]),
+                                   _ptr(out.get("scores") if want_scores else None),
+                                   _ptr(out.get("counts") if want_counts else None), _ptr(workspace),
+                                   workspace.numel(), _stream(stream))
+    _check(rc)
+    return out
 
 
 def predict_topk(h_prev, w_gate_next, bias_next=None, tokens_per_group=None, k=2,

@@ -78,6 +78,19 @@ def test_bad_arguments_are_rejected_without_a_launch(L):
     assert pr(fake, fake, None, 1, 1, fake, fake, 16, 16, 64, 8, 2, 1, fake, fake, None, None, fake,
               C.c_size_t(L.probe_route_topk_workspace_bytes(16, 64, 8, 2)), None) == -4   # needs more than the router
     assert L.probe_predict_topk_residual_workspace_bytes(16, 64, 8, 2, 16) > L.probe_route_topk_workspace_bytes(16, 64, 8, 2)
+    # group-limited gate
+    from paper_2602_00509_amd.probe import _Gating
+    rg = lambda gt, E=64, k=4, sb=fake: L.probe_route_grouped(
+        fake, fake, None, 1, 1, sb, C.byref(gt) if gt else None, 16, 64, E, k, fake, fake, None, None, fake, big, None)
+    assert rg(None) == -1 and "gating" in err()
+    assert rg(_Gating(2, 8, 4, 2, 1, 1.0)) == -1                         # unknown scoring
+    assert rg(_Gating(1, 7, 4, 2, 1, 1.0)) == -1                         # n_group does not divide E
+    assert rg(_Gating(1, 8, 9, 2, 1, 1.0)) == -1                         # topk_group > n_group
+    assert rg(_Gating(1, 8, 4, 9, 1, 1.0)) == -1                         # group_top > group size
+    assert rg(_Gating(1, 32, 1, 1, 1, 1.0)) == -1                        # k does not fit the allowed groups
+    assert rg(_Gating(1, 32, 4, 1, 1, 1.0)) == -2                        # n_group > 16
+    assert rg(_Gating(1, 8, 4, 2, 1, 1.0), sb=odd) == -3
+    assert rg(_Gating(1, 8, 4, 2, 1, 1.0), E=300) == -2
     # planner
     from paper_2602_00509_amd.probe import _PlannerParams
     pp = _PlannerParams(3, 3, 16, 0, 0, 0, 1)
