@@ -243,6 +243,25 @@ def combine(y, pair_row, w):
     return out
 
 
+def combine_shared(y, pair_row, w, shared, shared_scale=1.0):
+    """combine() plus shared_scale times the shared expert's output of every token (fp64)."""
+    y = _chk(y, np.float64)
+    H = y.shape[1]
+    pair_row = _chk(pair_row, np.int32)
+    T, k = pair_row.shape
+    w = _chk(w, np.float64, (T, k))
+    shared = _chk(shared, np.float64, (T, H))
+    if pair_row.size:
+        assert pair_row.max() < y.shape[0]
+    out = np.empty((T, H), np.float64)
+    rc = _load().oracle_combine_shared(_p(y, C.c_double), _p(pair_row, C.c_int32), _p(w, C.c_double),
+                                       _p(shared, C.c_double), C.c_double(float(shared_scale)), T, H, k,
+                                       _p(out, C.c_double))
+    if rc != 0:
+        raise ValueError("oracle combine_shared failed: %d" % rc)
+    return out
+
+
 def imbalance_ratio(rank_load) -> float:
     """Eq. 1: max rank load over mean rank load."""
     rank_load = _chk(rank_load, np.float64)

@@ -25,12 +25,14 @@
  *                         expert (silu(W1 x) * (W3 x), then W2).
  *   oracle_combine      - gate-weighted sum of the expert outputs of a token (the local part
  *                         of the combine step of the main track, Sec. 4.1).
+ *   oracle_combine_shared - the same plus a shared expert's output per token.
  *   oracle_imbalance_ratio - Eq. 1.
  *
  * Pins (tests/test_oracle_*.py): brute-force stable sort top-k, the Zipf closed form of a
  * bias-only softmax, uniform case and tie-break, torch fp64 library cross-checks, permutation
  * invariants and a hand-worked 6-token example, the closed-form per-replica counts,
- * identity-expert combine, plan invariance of the whole layer; for the residual: W2_hat = 0
+ * identity-expert combine (with a shared expert: (sum of weights + scale) x), plan invariance of the
+ * whole layer; for the residual: W2_hat = 0
  * gives the router bit for bit, a one-hot construction with a closed form, additivity in
  * W2_hat of the logits, and a torch fp64 cross-check.
  */
@@ -335,6 +337,26 @@ int oracle_combine(const double* y, const int32_t* pair_row, const double* w, in
       for (int h = 0; h < H; ++h) o[h] += ws * yr[h];
     }
   }
+  return 0;
+}
+
+/*
+ * Combine for a model with a shared expert (an expert every token uses, outside the gate; the
+ * output of the MoE block is the routed sum plus the shared expert's output, as in Eq. 12 of the
+ * DeepSeek-V3 technical report, without the residual connection, which lies outside the block):
+ *   out[t,:] = sum_s w[t,s] * y[pair_row[t,s],:]  +  shared_scale * shared[t,:]
+ * shared fp64 [T,H] is the shared expert's FFN output for every token (the grouped FFN run on x
+ * itself with one slot of T rows).
+ */
+int oracle_combine_shared(const double* y, const int32_t* pair_row, const double* w,
+                          const double* shared, double shared_scale, int T, int H, int k,
+                          double* out) {
+  if (!shared) return -1;
+  int rc = oracle_combine(y, pair_row, w, T, H, k, out);
+  if (rc != 0) return rc;
+  for (int t = 0; t < T; ++t)
+    for (int h = 0; h < H; ++h)
+      out[(size_t)t * H + h] += shared_scale * shared[(size_t)t * H + h];
   return 0;
 }
 

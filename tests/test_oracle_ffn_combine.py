@@ -92,6 +92,29 @@ def test_combine_identity_experts_and_remote(oracle):
     np.testing.assert_array_equal(o, [[25.5, 51.0]])
 
 
+def test_combine_with_a_shared_expert(oracle):
+    """Identity routed experts and an identity shared expert: out = (sum of weights + scale) * x; a hand case;
+    a zero shared output gives the plain combine."""
+    rng = np.random.default_rng(8)
+    T, H, E, k = 40, 8, 5, 2
+    x = _bits(rng.standard_normal((T, H)))
+    xf = wl.bf16_bits_to_f32(x).astype(np.float64)
+    w = (rng.standard_normal((E, H)) * 0.5).astype(np.float32)
+    r = oracle.route_topk(x, w, None, k=k, renormalize=False)
+    ident = dict(rep_off=np.arange(E + 1, dtype=np.int32), rep_slot=np.arange(E, dtype=np.int32),
+                 rep_weight=np.ones(E, np.int32))
+    p = oracle.permute(r["idx"], ident["rep_off"], ident["rep_slot"], ident["rep_weight"], E, x)
+    y = wl.bf16_bits_to_f32(p["xp"]).astype(np.float64)
+    out = oracle.combine_shared(y, p["pair_row"], r["w"], xf, 0.75)
+    np.testing.assert_allclose(out, (r["w"].sum(1, keepdims=True) + 0.75) * xf, rtol=1e-13, atol=1e-15)
+    np.testing.assert_array_equal(oracle.combine_shared(y, p["pair_row"], r["w"], np.zeros_like(xf), 3.0),
+                                  oracle.combine(y, p["pair_row"], r["w"]))
+    yy = np.array([[1.0, 2.0], [10.0, 20.0], [100.0, 200.0]])
+    o = oracle.combine_shared(yy, np.array([[2, -1, 0]], np.int32), np.array([[0.25, 0.125, 0.5]]),
+                              np.array([[4.0, -8.0]]), 0.5)
+    np.testing.assert_array_equal(o, [[27.5, 47.0]])      # 25.5 + 0.5*4, 51 + 0.5*(-8)
+
+
 def test_layer_plan_invariance(oracle):
     """Sec. 4.1 / 4.2: the main track is semantically equivalent to standard execution, so with
     every replica local the layer output under any plan equals the output with no replication."""
