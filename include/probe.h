@@ -268,6 +268,19 @@ int probe_grouped_ffn_gather(const void* x_bf16, const int32_t* row_pair, int T,
 int probe_combine(const void* y_bf16, const int32_t* pair_row, const float* topk_w, int T,
                   int H, int k, void* out_bf16, void* stream);
 
+/* Combine for a model with a shared expert (one that every token uses, outside the gate; the paper's
+ * Sec. 1 models include such, and the block's output is then the routed sum plus the shared expert's
+ * output, Eq. 12 of the DeepSeek-V3 technical report without the residual connection):
+ *   out[t,:] = sum_s topk_w[t,s] * y[pair_row[t,s],:]  +  shared_scale * shared_y[t,:]
+ * added after the k routed terms, same fp32 accumulator, one rounding to bf16.
+ *   shared_y_bf16  device, bf16 [T,H]: the shared expert's FFN output of every token, e.g. from
+ *                  probe_grouped_ffn on x itself with one slot of T rows (slot_offsets = {0, T})
+ * Other arguments and limits as probe_combine.
+ */
+int probe_combine_shared(const void* y_bf16, const int32_t* pair_row, const float* topk_w,
+                         const void* shared_y_bf16, float shared_scale, int T, int H, int k,
+                         void* out_bf16, void* stream);
+
 /* Router of layer L-1 and predictor of layer L (residual at its zero initialisation) in one pass
  * over the same hidden states: the predictor reads the tensor that the previous layer's own gate
  * reads (Sec. 4.2), so the two gates can be stacked into one operand.  Results are those of

@@ -72,6 +72,8 @@ def lib():
                                                [C.c_void_p] * 2 + [C.c_size_t, C.c_void_p])
         L.probe_grouped_ffn_gather.restype = C.c_int
         L.probe_combine.argtypes = [C.c_void_p] * 3 + [C.c_int] * 3 + [C.c_void_p] * 2
+        L.probe_combine_shared.restype = C.c_int
+        L.probe_combine_shared.argtypes = [C.c_void_p] * 4 + [C.c_float] + [C.c_int] * 3 + [C.c_void_p] * 2
         L.probe_route_grouped_workspace_bytes.restype = C.c_size_t
         L.probe_route_grouped_workspace_bytes.argtypes = [C.c_int] * 4
         L.probe_route_grouped.restype = C.c_int
@@ -461,6 +463,23 @@ def combine(y, pair_row, topk_w, *, out=None, stream=None):
     _want(out, torch.bfloat16, (T, H), "out")
     rc = lib().probe_combine(_ptr(y), _ptr(pair_row), _ptr(topk_w), T, H, k, _ptr(out),
                              _stream(stream))
+    _check(rc)
+    return out
+
+
+def combine_shared(y, pair_row, topk_w, shared_y, shared_scale=1.0, *, out=None, stream=None):
+    """probe_combine_shared: combine plus shared_scale * shared_y[t]; out bf16 [T,H]."""
+    T, k = pair_row.shape
+    H = y.shape[1]
+    _want(y, torch.bfloat16, (y.shape[0], H), "y")
+    _want(pair_row, torch.int32, (T, k), "pair_row")
+    _want(topk_w, torch.float32, (T, k), "topk_w")
+    _want(shared_y, torch.bfloat16, (T, H), "shared_y")
+    if out is None:
+        out = torch.empty((T, H), dtype=torch.bfloat16, device=y.device)
+    _want(out, torch.bfloat16, (T, H), "out")
+    rc = lib().probe_combine_shared(_ptr(y), _ptr(pair_row), _ptr(topk_w), _ptr(shared_y), C.c_float(shared_scale),
+                                    T, H, k, _ptr(out), _stream(stream))
     _check(rc)
     return out
 

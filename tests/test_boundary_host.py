@@ -58,6 +58,9 @@ def test_bad_arguments_are_rejected_without_a_launch(L):
     assert L.probe_combine(odd, fake, fake, 4, 64, 2, fake, None) == -3
     assert L.probe_combine(fake, fake, fake, -1, 64, 2, fake, None) == -1
     assert L.probe_combine(None, None, None, 0, 64, 2, None, None) == 0          # empty batch is legal
+    assert L.probe_combine_shared(fake, fake, fake, None, 1.0, 4, 64, 2, fake, None) == -1   # shared output missing
+    assert L.probe_combine_shared(fake, fake, fake, odd, 1.0, 4, 64, 2, fake, None) == -3
+    assert L.probe_combine_shared(fake, fake, fake, fake, 1.0, 4, 60, 2, fake, None) == -2
     # route / predict
     for fn in (L.probe_route_topk, L.probe_predict_topk):
         assert fn(fake, fake, None, 1, 1, 16, 64, 8, 9, 1, fake, fake, None, None, fake, big, None) == -1   # k > E

@@ -140,3 +140,36 @@ def test_deepseek_shape_sampled():
     # every token stays inside four groups of 32 experts
     grp = (g["idx"].cpu().numpy() // 32)
     assert max(len(set(r.tolist())) for r in grp) <= 4
+
+
+@pytest.mark.parametrize("T,H,F,k,scale", [(300, 128, 192, 4, 1.0), (65, 64, 64, 8, 0.5), (1, 64, 64, 1, 1.0)])
+def test_combine_with_shared_expert(T, H, F, k, scale):
+    """probe_combine_shared against the oracle; the shared expert's output comes from the grouped FFN run on x
+    itself with one slot of T rows (checked against the oracle's FFN too)."""
+    from gpu_util import bits_of, f64_of, rel_err, BF16_RTOL
+    rng = np.random.default_rng(T + k)
+    x = wl.f32_to_bf16_bits(rng.standard_normal((T, H)).astype(np.float32))
+    w13 = wl.f32_to_bf16_bits((rng.standard_normal((2 * F, H)) * 0.05).astype(np.float32))
+    w2 = wl.f32_to_bf16_bits((rng.standard_normal((H, F)) * 0.05).astype(np.float32))
+    n_rows = T * k // 2 + 3
+    y = wl.f32_to_bf16_bits(rng.standard_normal((n_rows, H)).astype(np.float32))
+    pair_row = rng.integers(-1, n_rows, size=(T, k)).astype(np.int32)
+    w = rng.random((T, k)).astype(np.float32)
+    so = np.array([0, T], np.int32)
+    d_x = dev_bf16(x)
+    shared = probe.grouped_ffn(d_x, torch.from_numpy(so).cuda(), probe.WeightTable([dev_bf16(w13)], [dev_bf16(w2)]))
+    out = probe.combine_shared(dev_bf16(y), torch.from_numpy(pair_row).cuda(), torch.from_numpy(w).cuda(), shared, scale)
+    plain = probe.combine(dev_bf16(y), torch.from_numpy(pair_row).cuda(), torch.from_numpy(w).cuda())
+    zero = probe.combine_shared(dev_bf16(y), torch.from_numpy(pair_row).cuda(), torch.from_numpy(w).cuda(),
+                                torch.zeros_like(shared), 3.0)
+    torch.cuda.synchronize()
+    o_shared = oracle.grouped_ffn(x, so, [w13], [w2])
+    assert rel_err(f64_of(shared), o_shared) <= BF16_RTOL
+    yf = wl.bf16_bits_to_f32(y).astype(np.float64)
+    # fed with the GPU's own (bf16) shared output: one fp32 accumulation and one rounding
+    o = oracle.combine_shared(yf, pair_row, w.astype(np.float64), f64_of(shared), scale)
+    assert rel_err(f64_of(out), o) <= 4e-3
+    # and end to end against the oracle's own shared expert
+    o2 = oracle.combine_shared(yf, pair_row, w.astype(np.float64), o_shared, scale)
+    assert rel_err(f64_of(out), o2) <= BF16_RTOL
+    assert torch.equal(zero, plain)
