@@ -84,6 +84,18 @@ __global__ __launch_bounds__(1024) void permute_scan_kernel(
   const int chunk = (U + 3) / 4;
   const int u0 = min(part * chunk, U), u1 = min(u0 + chunk, U);
   for (int s = tid; s < S; s += 1024) sc[s] = 0;
+  // this expert's replica range, its total weight and its first replica are fetched now, under
+  // the histogram passes
+  int lo = 0, hi = 0, P = 0, w_first = 0, s_first = -1;
+  if (part == 0 && e < E) {
+    lo = rep_off[e];
+    hi = rep_off[e + 1];
+    for (int i = lo; i < hi; ++i) P += rep_weight[i];
+    if (hi > lo) {
+      w_first = rep_weight[lo];
+      s_first = rep_slot[lo];
+    }
+  }
   int tot = 0;
   if (e < E) {
     int u = u0;
@@ -122,15 +134,12 @@ __global__ __launch_bounds__(1024) void permute_scan_kernel(
   if (part == 0 && e < E) {
     const int n_e = part_tot[0][e] + part_tot[1][e] + part_tot[2][e] + part_tot[3][e];
     // rows each replica of this expert receives: floor(n/P) w_i + clamp(n mod P - c_{i-1}, 0, w_i)
-    int lo = rep_off[e], hi = rep_off[e + 1];
-    int P = 0;
-    for (int i = lo; i < hi; ++i) P += rep_weight[i];
     if (P > 0) {
       int full = n_e / P, rem = n_e - full * P, cum = 0;
       for (int i = lo; i < hi; ++i) {
-        int wgt = rep_weight[i];
+        int wgt = i == lo ? w_first : rep_weight[i];
         int part_rows = min(max(rem - cum, 0), wgt);
-        int slot = rep_slot[i];
+        int slot = i == lo ? s_first : rep_slot[i];
         if (slot >= 0 && slot < S) sc[slot] = full * wgt + part_rows;
         cum += wgt;
       }
@@ -188,9 +197,23 @@ __global__ __launch_bounds__(kPermWaves* kWave) void permute_index_kernel(
   int w = threadIdx.x / kWave, lane = lane_id();
   volatile int32_t* cnt_w = cnt_mem[w];  // volatile: keep every lane's read before the leader's update
   long base = (static_cast<long>(blockIdx.x) * kPermWaves + w) * kSegPairs;
+  // every global load that depends on nothing is issued first, so that their latencies overlap:
+  // this wave's pairs, the block's bases, the size of the replica list
+  int seg_e[kSegIters];
+#pragma unroll
+  for (int it = 0; it < kSegIters; ++it) {
+    long p = base + it * kWave + lane;
+    seg_e[it] = p < N ? topk_idx[p] : -1;
+  }
+  int start[PROBE_MAX_EXPERTS / kWave];
+#pragma unroll
+  for (int i = 0; i < PROBE_MAX_EXPERTS / kWave; ++i) {
+    int e = lane + i * kWave;
+    start[i] = e < E ? blk_base[static_cast<long>(blockIdx.x) * E + e] : 0;
+  }
+  const int R = rep_off[E];
   // the plan, once per workgroup: replica lists (in LDS when they fit), replica range and total
   // weight of every expert, slot offsets
-  const int R = rep_off[E];
   const bool staged = R <= kRepLds;
   if (staged)
     for (int i = threadIdx.x; i < R; i += kPermWaves * kWave) {
@@ -200,37 +223,32 @@ __global__ __launch_bounds__(kPermWaves* kWave) void permute_index_kernel(
   const int32_t* rw = staged ? s_rw : rep_weight;  // flat pointers: LDS or global
   const int32_t* rs = staged ? s_rs : rep_slot;
   for (int e = threadIdx.x; e < E; e += kPermWaves * kWave) {
-    int lo = rep_off[e], hi = rep_off[e + 1], P = 0;
-    for (int i = lo; i < hi; ++i) P += rep_weight[i];
-    e_lo[e] = lo;
-    e_hi[e] = hi;
-    e_P[e] = P;
+    e_lo[e] = rep_off[e];
+    e_hi[e] = rep_off[e + 1];
   }
   for (int i = threadIdx.x; i <= S; i += kPermWaves * kWave) s_off[i] = slot_offsets[i];
-  // counts of this wave's own segment (the same walk as in step 1), kept in registers
+  // counts of this wave's own segment (the same walk as in step 1)
   for (int e = lane; e < E; e += kWave) cnt_w[e] = 0;
-  int seg_e[kSegIters];
 #pragma unroll
   for (int it = 0; it < kSegIters; ++it) {
-    long p = base + it * kWave + lane;
-    int e = p < N ? topk_idx[p] : -1;
-    seg_e[it] = e;
+    int e = seg_e[it];
     bool valid = static_cast<unsigned>(e) < static_cast<unsigned>(E);
     uint64_t m = match_key8(e, valid);
     if (valid && (m & lanemask_lt()) == 0) cnt_w[e] += __popcll(m);
   }
   __syncthreads();
+  // total weight of every expert, from the staged list when there is one
+  for (int e = threadIdx.x; e < E; e += kPermWaves * kWave) {
+    int P = 0;
+    for (int i = e_lo[e]; i < e_hi[e]; ++i) P += rw[i];
+    e_P[e] = P;
+  }
   // arrival rank at the start of this wave's segment: block base + counts of the earlier waves
-  int start[PROBE_MAX_EXPERTS / kWave];
 #pragma unroll
   for (int i = 0; i < PROBE_MAX_EXPERTS / kWave; ++i) {
     int e = lane + i * kWave;
-    int v = 0;
-    if (e < E) {
-      v = blk_base[static_cast<long>(blockIdx.x) * E + e];
-      for (int q = 0; q < w; ++q) v += cnt_mem[q][e];
-    }
-    start[i] = v;
+    if (e < E)
+      for (int q = 0; q < w; ++q) start[i] += cnt_mem[q][e];
   }
   __syncthreads();
 #pragma unroll
