@@ -302,9 +302,15 @@ def main():
         e1.record()
         torch.cuda.synchronize()
         st = pl["stats"].cpu().tolist()
+        # Eq. 1 on token loads: before = every expert at home, after = the plan's assignment
+        per_expert = np.stack(rows).astype(np.int64).sum(0)
+        home_load = per_expert.reshape(ep, cfg.E_loc).sum(1)
+        mean_load = float(per_expert.sum()) / ep
         result["planner"] = {"us_per_call": e0.elapsed_time(e1) * 1e3 / 20, "ranks": ep, "experts": E,
                              "params": kw, "moves": st[3], "bottleneck_latency_before": st[0],
-                             "bottleneck_latency_after": st[1]}
+                             "bottleneck_latency_after": st[1],
+                             "imbalance_ratio_before": float(home_load.max()) / mean_load,
+                             "imbalance_ratio_after": float(st[2]) / mean_load}
 
     # the group-limited gate (sigmoid scores, E / 32 groups of 32 experts, half of them allowed) on the same
     # inputs, timed on its own next to the plain router; not part of `value`
