@@ -375,6 +375,15 @@ def measure_peaks(torch, probe, dev):
     t = timed(lambda: dst.copy_(src), 5)
     res["copy_read_plus_write_gbps"] = 2 * src.numel() * 4 / t / 1e9
     del src, dst, out
+    # context only: the vendor GEMM library (through torch.matmul) on one plain bf16 GEMM with the FFN's
+    # first-GEMM shape and N(0,1) / N(0,0.02) operands; none of the library's code is on the product path
+    M, N, K = 16384, 4096, 7168
+    a = torch.empty((M, K), device=dev, dtype=torch.float32).normal_(0.0, 1.0).to(torch.bfloat16)
+    b = torch.empty((N, K), device=dev, dtype=torch.float32).normal_(0.0, 0.02).to(torch.bfloat16)
+    c = torch.empty((M, N), device=dev, dtype=torch.bfloat16)
+    t = timed(lambda: torch.matmul(a, b.t(), out=c), 10)
+    res["vendor_gemm_16384x4096x7168_tflops"] = 2.0 * M * N * K / t / 1e12
+    del a, b, c
     return res
 
 
