@@ -79,3 +79,22 @@ def test_full_configs_sampled(oracle, probe, G, cid, batch):
     G.run_layer_parity(oracle, probe, wl.CONFIGS[cid], batch=batch, route_sample=512, ffn_sample=48,
                        seed=cid, report=REPORT)
     _flush_report()
+
+
+# The two models the paper evaluates (Sec. 5): GPT-OSS-120B-shaped (128 experts, top-4, hidden and FFN width
+# 2880, neither a multiple of 256) and Qwen3-MoE-235B-shaped (128 experts, top-8, hidden 4096, FFN width
+# 1536), one rank's share at ep = 8 with two replica slots, a 2048-token prefill chunk.  Shapes only: the
+# gate is the renormalised softmax top-k (the GPT-OSS form, softmax over the chosen logits, equals it).
+PAPER_MODELS = [
+    dict(T=2048, H=2880, E=128, k=4, F=2880, E_loc=16, n_rep=2, ep=8, chunk=0),
+    dict(T=2048, H=4096, E=128, k=8, F=1536, E_loc=16, n_rep=2, ep=8, chunk=0),
+]
+
+
+@pytest.mark.parametrize("i", range(len(PAPER_MODELS)))
+def test_shapes_of_the_models_the_paper_evaluates(oracle, probe, G, i):
+    cfg = wl.small_config(cid=300 + i, **PAPER_MODELS[i])
+    print("case paper model shape", i, PAPER_MODELS[i], flush=True)
+    G.run_layer_parity(oracle, probe, cfg, batch=0, route_sample=256, ffn_sample=32, seed=300 + i, report=REPORT)
+    _flush_report()
+
