@@ -41,7 +41,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--config", type=int, default=3, help="benchmark configuration (1-5)")
+    ap.add_argument("--config", type=int, default=3, help="benchmark configuration (1-5; 6, 7 = the shapes of the models the paper evaluates)")
     ap.add_argument("--batches", type=int, default=0, help="distinct batches to rotate over (0 = config default)")
     ap.add_argument("--residual-width", type=int, default=0,
                     help="width D of the predictor's residual MLP (Eq. 7); 0 = residual at its zero initialisation, "

@@ -55,7 +55,12 @@ CONFIGS = {
     3: LayerConfig(3, "deepseek-v3-shaped-shard", 8192, 7168, 256, 8, 2048, 32, 4, 1.1, 0, 8, 8),
     4: LayerConfig(4, "qwen3-moe-shaped-decode", 128, 4096, 128, 8, 1536, 16, 2, 1.1, 0, 16, 8),
     5: LayerConfig(5, "predictor-stress", 16384, 7168, 256, 8, 2048, 64, 0, 1.5, 1024, 2, 4),
+    # beyond the five benchmark configurations: one rank's share (ep = 8, two replica slots) of the two
+    # models the paper evaluates (Sec. 5), at a prefill chunk of 8192 tokens per rank; shapes only
+    6: LayerConfig(6, "gpt-oss-120b-shaped-prefill", 8192, 2880, 128, 4, 2880, 16, 2, 1.1, 0, 8, 8),
+    7: LayerConfig(7, "qwen3-moe-235b-shaped-prefill", 8192, 4096, 128, 8, 1536, 16, 2, 1.1, 0, 8, 8),
 }
+ROTATING_HOT_SET = (3, 6, 7)   # one base popularity order, rotated by E_loc experts per batch
 
 
 def small_config(T=96, H=128, E=16, k=4, F=192, E_loc=4, n_rep=2, zipf_s=1.1, chunk=32,
@@ -113,12 +118,12 @@ def zipf_bias(cfg: LayerConfig, batch: int = 0, layer: int = 0) -> np.ndarray:
 
     The popularity order is a seeded permutation.  Configurations with ``chunk`` draw a fresh
     order per chunk of tokens (hot-spot migration inside one call).  Configuration 3 rotates
-    one base order by E_loc experts per batch, so the hot set visits every virtual rank.
+    one base order by E_loc experts per batch, so the hot set visits every virtual rank (so do 6 and 7).
     Configurations 1, 4 draw a fresh order per batch (per decode step)."""
     G, E = cfg.G, cfg.E
     b = np.empty((G, E), np.float32)
     for g in range(G):
-        if cfg.cid == 3:
+        if cfg.cid in ROTATING_HOT_SET:
             base = _rng(cfg, 3, layer).permutation(E)
             order = np.roll(base, cfg.E_loc * batch)
         else:
