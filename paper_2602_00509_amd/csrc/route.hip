@@ -279,6 +279,31 @@ __device__ __forceinline__ int row_min_i(int v) {
   return v;
 }
 
+// Pairwise (tree) reductions over a register array: depth log2(N) instead of a chain of N - 1
+// dependent operations; max and min are exact, so the result does not depend on the order.
+template <int N>
+__device__ __forceinline__ float tree_max(const float (&v)[N]) {
+  float t[N];
+#pragma unroll
+  for (int i = 0; i < N; ++i) t[i] = v[i];
+#pragma unroll
+  for (int st = 1; st < N; st *= 2)
+#pragma unroll
+    for (int i = 0; i + st < N; i += 2 * st) t[i] = fmaxf(t[i], t[i + st]);
+  return t[0];
+}
+template <int N>
+__device__ __forceinline__ int tree_min(const int (&v)[N]) {
+  int t[N];
+#pragma unroll
+  for (int i = 0; i < N; ++i) t[i] = v[i];
+#pragma unroll
+  for (int st = 1; st < N; st *= 2)
+#pragma unroll
+    for (int i = 0; i + st < N; i += 2 * st) t[i] = min(t[i], t[i + st]);
+  return t[0];
+}
+
 // Logit row pieces of U tokens: the KS split-K slices are added in ascending order, then the bias row
 // of the token's group.  Lane `sub` receives the experts 64*i + 4*sub + j; entries past E are zero.
 template <int NV, int U>
@@ -393,10 +418,7 @@ __global__ __launch_bounds__(256) void gate_softmax_topk_kernel(
         v = (v >= fmin_) ? v : fmin_;
         l[u][i] = (e < E) ? v : ninf;
       }
-      float m = l[u][0];
-#pragma unroll
-      for (int i = 1; i < NL; ++i) m = fmaxf(m, l[u][i]);
-      mx[u] = row_max(m);
+      mx[u] = row_max(tree_max(l[u]));
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -436,18 +458,15 @@ __global__ __launch_bounds__(256) void gate_softmax_topk_kernel(
     for (int s = 0; s < k; ++s) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        float m = l[u][0];
-#pragma unroll
-        for (int i = 1; i < NL; ++i) m = fmaxf(m, l[u][i]);
-        const float best = row_max(m);
+        const float best = row_max(tree_max(l[u]));
         // lowest expert id among the entries that hold the row maximum
-        int cand = INT_MAX;
+        int cand[NL];
 #pragma unroll
-        for (int i = NL - 1; i >= 0; --i) {
+        for (int i = 0; i < NL; ++i) {
           const int e = 64 * (i >> 2) + 4 * sub + (i & 3);
-          cand = (l[u][i] == best) ? e : cand;
+          cand[i] = (l[u][i] == best) ? e : INT_MAX;
         }
-        const int be = row_min_i(cand);
+        const int be = row_min_i(tree_min(cand));
         // its owner marks it taken
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
@@ -539,10 +558,7 @@ __global__ __launch_bounds__(256) void gate_grouped_topk_kernel(
 #pragma unroll
         for (int i = 0; i < NL; ++i) sc[u][i] = 1.f / (1.f + expf(-sc[u][i]));  // 0 past E
       } else {
-        float m = sc[u][0];
-#pragma unroll
-        for (int i = 1; i < NL; ++i) m = fmaxf(m, sc[u][i]);
-        m = row_max(m);
+        const float m = row_max(tree_max(sc[u]));
         float sum = 0.f;
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
@@ -671,17 +687,14 @@ __global__ __launch_bounds__(256) void gate_grouped_topk_kernel(
     for (int s = 0; s < k; ++s) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        float m = c[u][0];
+        const float best = row_max(tree_max(c[u]));
+        int cand[NL];
 #pragma unroll
-        for (int i = 1; i < NL; ++i) m = fmaxf(m, c[u][i]);
-        const float best = row_max(m);
-        int cand = INT_MAX;
-#pragma unroll
-        for (int i = NL - 1; i >= 0; --i) {
+        for (int i = 0; i < NL; ++i) {
           const int e = 64 * (i >> 2) + 4 * sub + (i & 3);
-          cand = (c[u][i] == best) ? e : cand;
+          cand[i] = (c[u][i] == best) ? e : INT_MAX;
         }
-        const int be = row_min_i(cand);
+        const int be = row_min_i(tree_min(cand));
         float mine = ninf;  // the owner's score of the winner, without the selection bias
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
