@@ -66,15 +66,27 @@ def _cases():
         F = int(rng.choice([64, 128, 192, 256, 448]))
         E = int(rng.choice([2, 3, 5, 8, 17, 40, 64, 130, 200]))
         k = int(rng.integers(1, min(8, E) + 1))
-        out.append((i, T, H, E, k, F))
+        out.append((i, T, H, E, k, F, 1.0, 0, 24))
+    # a second, wider draw: one expert, the largest expert counts, strong and no skew, bias groups inside the
+    # call, one to sixty local slots
+    for i in range(14, 40):
+        T = int(rng.choice([1, 3, 17, 64, 65, 100, 128, 129, 255, 256, 257, 383, 512, 513, 700, 1024, 1300, 2049]))
+        H = int(rng.choice([64, 128, 192, 256, 320, 448, 512, 704]))
+        F = int(rng.choice([64, 128, 192, 256, 320, 448, 576]))
+        E = int(rng.choice([1, 2, 3, 4, 7, 8, 16, 33, 64, 100, 128, 129, 255, 256]))
+        k = int(rng.integers(1, min(8, E) + 1))
+        out.append((i, T, H, E, k, F, float(rng.choice([0.0, 1.0, 2.0])), int(rng.choice([0, 0, 64])),
+                    int(rng.choice([1, 4, 24, 60]))))
     return out
 
 
-@pytest.mark.parametrize("case,T,H,E,k,F", _cases())
-def test_random_shape_and_plan(oracle, probe, G, case, T, H, E, k, F):
-    print("case random %d: T=%d H=%d E=%d k=%d F=%d" % (case, T, H, E, k, F), flush=True)
-    cfg = wl.small_config(T=T, H=H, E=E, k=k, F=F, E_loc=min(E, 4), n_rep=0, zipf_s=1.0, chunk=0, ep=1, cid=200 + case)
+@pytest.mark.parametrize("case,T,H,E,k,F,zipf_s,chunk,max_slots", _cases())
+def test_random_shape_and_plan(oracle, probe, G, case, T, H, E, k, F, zipf_s, chunk, max_slots):
+    print("case random %d: T=%d H=%d E=%d k=%d F=%d zipf=%.1f chunk=%d slots<=%d" % (case, T, H, E, k, F, zipf_s, chunk,
+                                                                                    max_slots), flush=True)
+    cfg = wl.small_config(T=T, H=H, E=E, k=k, F=F, E_loc=min(E, 4), n_rep=0, zipf_s=zipf_s, chunk=chunk, ep=1,
+                          cid=200 + case)
     rng = np.random.default_rng(case)
-    plan = random_plan(rng, E, max_slots=24)
+    plan = random_plan(rng, E, max_slots=max_slots)
     res = G.run_layer_parity(oracle, probe, cfg, batch=0, plan_fn=lambda c, counts: plan, renormalize=bool(case % 2))
     assert res["n_local"] <= T * k
