@@ -289,3 +289,41 @@ def test_ffn_with_rows_gathered_on_load_equals_ffn_on_the_permuted_copy(oracle, 
                          plan["num_slots"], L.x)
     ref = oracle.grouped_ffn(o_p["xp"], o_p["slot_offsets"], [w[0] for w in ws], [w[1] for w in ws])
     assert G.rel_err(G.f64_of(y1)[:nl], ref) < G.BF16_RTOL
+
+
+def test_largest_slot_and_expert_counts(oracle, probe, G):
+    """The limits of the build at once: 256 experts, top-8, 1024 weight slots (four local copies of every
+    expert with unequal shares).  Permute is checked completely, the FFN on a row sample from every slot."""
+    E, k, T, H, F, S = 256, 8, 2048, 64, 64, 1024
+    cfg = wl.small_config(T=T, H=H, E=E, k=k, F=F, E_loc=E, n_rep=0, zipf_s=1.0, chunk=0, ep=1, cid=95)
+    L, r = _layer(G, probe, cfg)
+    rep_off = np.arange(0, 4 * E + 1, 4, dtype=np.int32)
+    rng = np.random.default_rng(95)
+    rep_slot = rng.permutation(S).astype(np.int32)                  # copies of an expert sit in scattered slots
+    rep_weight = rng.integers(0, 4, size=S).astype(np.int32)
+    rep_weight[::4] = np.maximum(rep_weight[::4], 1)                # every expert keeps a positive share
+    slot_expert = np.empty(S, np.int32)
+    slot_expert[rep_slot] = np.repeat(np.arange(E, dtype=np.int32), 4)
+    plan = probe.Plan(rep_off, rep_slot, rep_weight, S)
+    p = probe.permute(r["idx"], plan, L.d_x)
+    torch.cuda.synchronize()
+    idx = r["idx"].cpu().numpy()
+    o = oracle.permute(idx, rep_off, rep_slot, rep_weight, S, L.x)
+    for key in ("slot_counts", "slot_offsets", "pair_row"):
+        np.testing.assert_array_equal(p[key].cpu().numpy(), o[key])
+    nl = int(o["n_local"])
+    assert int(p["n_local"].item()) == nl == T * k
+    np.testing.assert_array_equal(p["row_pair"].cpu().numpy()[:nl], o["row_pair"][:nl])
+    np.testing.assert_array_equal(G.bits_of(p["xp"][:nl]), o["xp"][:nl])
+    ws = wl.expert_weights_many(cfg, list(range(E)))
+    d_w = [(G.dev_bf16(a), G.dev_bf16(b)) for a, b in ws]
+    tab = probe.WeightTable([d_w[e][0] for e in slot_expert], [d_w[e][1] for e in slot_expert])
+    y = probe.grouped_ffn(p["xp"], p["slot_offsets"], tab)
+    torch.cuda.synchronize()
+    so = o["slot_offsets"]
+    rows = np.unique(np.concatenate([so[:-1][np.diff(so) > 0], so[1:][np.diff(so) > 0] - 1,
+                                     rng.choice(nl, 512, replace=False)])).astype(np.int32)
+    ref = oracle.grouped_ffn(o["xp"], so, [ws[e][0] for e in slot_expert], [ws[e][1] for e in slot_expert], rows=rows)
+    got = G.f64_of(y[torch.from_numpy(rows.astype(np.int64)).cuda()])
+    assert G.rel_err(got, ref) < G.BF16_RTOL
+    assert (np.diff(so) == 0).any() and (np.diff(so) > 64).any()    # empty slots and slots of several tiles' worth
