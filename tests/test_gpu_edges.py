@@ -327,3 +327,13 @@ def test_largest_slot_and_expert_counts(oracle, probe, G):
     got = G.f64_of(y[torch.from_numpy(rows.astype(np.int64)).cuda()])
     assert G.rel_err(got, ref) < G.BF16_RTOL
     assert (np.diff(so) == 0).any() and (np.diff(so) > 64).any()    # empty slots and slots of several tiles' worth
+
+
+def test_more_tokens_than_one_pass_of_any_grid(oracle, probe, G):
+    """140001 tokens: the top-k kernel's grid covers 131072 tokens per pass and wraps, permute walks 274 blocks
+    of pairs, the FFN table holds hundreds of tiles.  Routing and permutation are checked completely, the
+    floating-point stages on samples."""
+    cfg = wl.small_config(T=140001, H=64, E=16, k=2, F=64, E_loc=8, n_rep=2, zipf_s=1.1, chunk=0, ep=2, cid=96)
+    print("case many tokens", flush=True)
+    res = G.run_layer_parity(oracle, probe, cfg, batch=0, route_sample=None, ffn_sample=64, seed=96)
+    assert res["n_local"] > 100000
