@@ -259,6 +259,14 @@ def main():
         "ffn_weight_stream_gbps": ffn_bytes / mean_ms["ffn"] / 1e6,
         "stage_hbm_gbps": gbps,
         "stage_frac_hbm_peak": {n: v / PEAK_HBM_GBPS for n, v in gbps.items()},
+        # the gate is a contraction of 2*T*H*E flops that runs on the matrix cores as three bf16 planes (fp32
+        # weights kept exact), so its arithmetic roof is the bf16 MFMA peak over plane-expanded flops; at E >= 128
+        # that roof binds, at E = 8 the HBM one does
+        "gate_binding_roof": "mfma" if E >= 64 else "hbm",
+        "gate_plane_expanded_tflops": {n: 3 * 2.0 * T * H * E / (mean_ms[n] * 1e-3) / 1e12
+                                       for n in ("predict", "route") if mean_ms[n] > 0},
+        "gate_frac_bf16_mfma_peak": {n: 3 * 2.0 * T * H * E / (mean_ms[n] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS
+                                     for n in ("predict", "route") if mean_ms[n] > 0},
         "roofline": {"kernel": "probe_grouped_ffn (ffn_gemm1_kernel + ffn_gemm2_kernel)", "bound": "mfma",
                      "achieved": ffn_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": ffn_tflops / PEAK_BF16_TFLOPS,
