@@ -234,6 +234,10 @@ def main():
     act_mean = float(np.mean([active_slots[i % nb] for i in range(args.steps)]))
     ffn_bytes = act_mean * 3 * H * F * 2 + 2 * nl_mean * H * 2   # weights of non-empty slots once + xp + y
 
+    # gate GEMMs per stage: the fused call runs both gates under "predict"
+    gates = {"predict": 2, "route": 0} if args.fused_route_predict else {"predict": 1, "route": 1}
+    gate_tflops = {n: g * 3 * 2.0 * T * H * E / (mean_ms[n] * 1e-3) / 1e12 for n, g in gates.items() if g}
+
     result = {
         "metric": "moe_layer_tokens_per_s",
         "value": T * args.steps / elapsed,
@@ -263,10 +267,8 @@ def main():
         # weights kept exact), so its arithmetic roof is the bf16 MFMA peak over plane-expanded flops; at E >= 128
         # that roof binds, at E = 8 the HBM one does
         "gate_binding_roof": "mfma" if E >= 64 else "hbm",
-        "gate_plane_expanded_tflops": {n: 3 * 2.0 * T * H * E / (mean_ms[n] * 1e-3) / 1e12
-                                       for n in ("predict", "route") if mean_ms[n] > 0},
-        "gate_frac_bf16_mfma_peak": {n: 3 * 2.0 * T * H * E / (mean_ms[n] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS
-                                     for n in ("predict", "route") if mean_ms[n] > 0},
+        "gate_plane_expanded_tflops": gate_tflops,
+        "gate_frac_bf16_mfma_peak": {n: v / PEAK_BF16_TFLOPS for n, v in gate_tflops.items()},
         "roofline": {"kernel": "probe_grouped_ffn (ffn_gemm1_kernel + ffn_gemm2_kernel)", "bound": "mfma",
                      "achieved": ffn_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": ffn_tflops / PEAK_BF16_TFLOPS,
