@@ -48,7 +48,10 @@
  * Pins (tests/test_oracle_planner.py): conservation sum_rt n = n-hat and validity
  * n_{e,r} > 0 => P_{r,e} = 1 (the constraints of the optimisation problem), the budgets, a
  * non-increasing bottleneck latency, locality, the fixed point on balanced input, and two
- * hand-worked three-rank examples whose every number is written out in the test.
+ * hand-worked three-rank examples whose every number is written out in the test.  The two views
+ * of the result (oracle_plan_for_rank: what a rank receives; oracle_plan_dispatch: what a rank
+ * sends) are pinned by the hand-worked example, by each other (same replica lists, the origins'
+ * weights add up to the receiver's) and by locality (an origin that holds a copy keeps its tokens).
  */
 #include <stdint.h>
 #include <stdlib.h>
@@ -269,3 +272,40 @@ int oracle_plan_for_rank(const int32_t* n, const int32_t* delta_in, int R, int E
   rep_off[E] = pos;
   return 0;
 }
+
+/*
+ * The same plan as a SOURCE rank applies it to its own tokens ahead of the dispatch exchange
+ * (assignment A of Sec. 3.1 with the locality-first rule of Sec. 4.3): in the layout of
+ * probe_permute with the R ranks in the place of weight slots.  Expert e lists the ranks that
+ * hold a copy of it, ascending; rep_rank = that rank (the "slot"); rep_weight = n[rs][e][r], the
+ * tokens that originate on rs and are planned for the copy on r.  When no token of e was predicted
+ * from this origin, an unforeseen one stays on rs if rs holds a copy and goes to e's home otherwise
+ * (weight 1 there).  The replica lists are those of oracle_plan_for_rank (same rep_off).
+ */
+int oracle_plan_dispatch(const int32_t* n, const int32_t* delta_in, int R, int E, int E_loc,
+                         int max_replicas, int rs, int32_t* rep_off, int32_t* rep_rank,
+                         int32_t* rep_weight) {
+  if (rs < 0 || rs >= R) return -1;
+  int pos = 0;
+  for (int e = 0; e < E; ++e) {
+    rep_off[e] = pos;
+    int64_t planned = 0;
+    int home_pos = pos, own_pos = -1;
+    for (int r = 0; r < R; ++r) {
+      int here = (e / E_loc == r);
+      if (here) home_pos = pos;
+      for (int i = 0; i < max_replicas && !here; ++i)
+        if (delta_in[(size_t)r * max_replicas + i] == e) here = 1;
+      if (!here) continue;
+      if (r == rs) own_pos = pos;
+      rep_rank[pos] = r;
+      rep_weight[pos] = n[IDX(rs, e, r)];
+      planned += n[IDX(rs, e, r)];
+      pos += 1;
+    }
+    if (planned == 0) rep_weight[own_pos >= 0 ? own_pos : home_pos] = 1;
+  }
+  rep_off[E] = pos;
+  return 0;
+}
+

@@ -157,3 +157,49 @@ def test_plan_for_rank_layout(oracle):
     # the per-replica token split that permute derives from these weights conserves every expert's tokens
     for e in range(3):
         assert p["rep_weight"][p["rep_off"][e]:p["rep_off"][e + 1]].sum() == nh[:, e].sum()
+
+
+def test_plan_dispatch_hand_worked_and_ties_to_the_receiving_plan(oracle):
+    """The plan as a source rank applies it to its own tokens (ranks in the place of slots).
+    Hand-worked on the state after the first move of the three-rank example: expert 0 is held by ranks 0
+    (home) and 1 (copy); origin 2's 40 tokens of it are planned 17 on rank 0 and 23 on rank 1; its own expert 2
+    keeps its 10 tokens at home; it predicted nothing for expert 1, whose home is rank 1."""
+    nh = np.array([[20, 0, 0], [30, 10, 0], [40, 0, 10]], np.int32)
+    r1 = oracle.plan_greedy(nh, 1, max_replicas=2, budget=2, k_max=1)
+    d2 = oracle.plan_dispatch(r1["n"], r1["delta_in"], 1, rank=2)
+    np.testing.assert_array_equal(d2["rep_off"], [0, 2, 3, 4])
+    np.testing.assert_array_equal(d2["rep_slot"], [0, 1, 1, 2])           # destination ranks
+    np.testing.assert_array_equal(d2["rep_weight"], [17, 23, 1, 10])
+    assert d2["num_slots"] == 3
+    # origin 1 holds the copy: locality first, all 30 of its tokens of expert 0 stay on rank 1
+    d1 = oracle.plan_dispatch(r1["n"], r1["delta_in"], 1, rank=1)
+    np.testing.assert_array_equal(d1["rep_weight"], [0, 30, 10, 1])
+    np.testing.assert_array_equal(d1["rep_slot"], [0, 1, 1, 2])
+    # random cases: same replica lists as the receiving plan, the weights of all origins add up to the
+    # receiving plan's weights, every origin's weights add up to what it predicted, and an origin that holds
+    # a copy of an expert keeps its own tokens of it
+    for seed, R, E, E_loc in ((1, 4, 16, 4), (2, 8, 64, 8), (3, 5, 20, 4)):
+        nh = _random_nhat(seed, R, E)
+        r = oracle.plan_greedy(nh, E_loc, max_replicas=3, budget=2, k_max=16, n0=16, g_num=1, g_den=4)
+        assert r["n_moves"] >= 2
+        recv = oracle.plan_for_rank(r["n"], r["delta_in"], E_loc, rank=0)
+        total = np.zeros_like(recv["rep_weight"])
+        for rs in range(R):
+            d = oracle.plan_dispatch(r["n"], r["delta_in"], E_loc, rank=rs)
+            np.testing.assert_array_equal(d["rep_off"], recv["rep_off"])
+            for e in range(E):
+                sl = slice(d["rep_off"][e], d["rep_off"][e + 1])
+                w, ranks = d["rep_weight"][sl], d["rep_slot"][sl]
+                assert (np.diff(ranks) > 0).all() and (e // E_loc) in ranks
+                if nh[rs, e] > 0:
+                    assert w.sum() == nh[rs, e]
+                    if rs in ranks:
+                        assert w[list(ranks).index(rs)] == nh[rs, e]          # locality first
+                    total[sl] += w
+                else:
+                    assert w.sum() == 1 and w[list(ranks).index(rs if rs in ranks else e // E_loc)] == 1
+        planned = nh.sum(0)
+        for e in range(E):
+            sl = slice(recv["rep_off"][e], recv["rep_off"][e + 1])
+            if planned[e] > 0:
+                np.testing.assert_array_equal(total[sl], recv["rep_weight"][sl])
