@@ -162,22 +162,26 @@ def route_grouped(x_bits, w_gate, bias=None, tokens_per_group=None, select_bias=
 
 
 def plan_dispatch(n, delta_in, E_loc, rank):
-    """The plan of plan_greedy as source rank ``rank`` applies it to its own tokens: ranks in the place of slots."""
+    """The plan of plan_greedy as source rank ``rank`` applies it to its own tokens: one slot per
+    (destination rank, expert copy), numbered by rank first; rank_off [R+1] delimits the ranks' slots."""
     n = _chk(n, np.int32)
     R, E, _ = n.shape
     delta_in = _chk(delta_in, np.int32)
     max_replicas = delta_in.shape[1]
     rep_off = np.zeros((E + 1,), np.int32)
     cap = E + R * max_replicas
-    rep_rank = np.full((cap,), -1, np.int32)
+    rep_slot = np.full((cap,), -1, np.int32)
     rep_weight = np.zeros((cap,), np.int32)
+    rank_off = np.zeros((R + 1,), np.int32)
+    slot_expert = np.full((cap,), -1, np.int32)
     rc = _load().oracle_plan_dispatch(_p(n, C.c_int32), _p(delta_in, C.c_int32), R, E, int(E_loc), max_replicas,
-                                      int(rank), _p(rep_off, C.c_int32), _p(rep_rank, C.c_int32),
-                                      _p(rep_weight, C.c_int32))
+                                      int(rank), _p(rep_off, C.c_int32), _p(rep_slot, C.c_int32),
+                                      _p(rep_weight, C.c_int32), _p(rank_off, C.c_int32), _p(slot_expert, C.c_int32))
     if rc != 0:
         raise ValueError("oracle plan_dispatch failed: %d" % rc)
     used = int(rep_off[E])
-    return dict(rep_off=rep_off, rep_slot=rep_rank[:used].copy(), rep_weight=rep_weight[:used].copy(), num_slots=R)
+    return dict(rep_off=rep_off, rep_slot=rep_slot[:used].copy(), rep_weight=rep_weight[:used].copy(), num_slots=cap,
+                rank_off=rank_off, slot_expert=slot_expert[:used].copy())
 
 
 def permute(topk_idx, rep_off, rep_slot, rep_weight, num_slots, x_bits=None):

@@ -275,30 +275,50 @@ int oracle_plan_for_rank(const int32_t* n, const int32_t* delta_in, int R, int E
 
 /*
  * The same plan as a SOURCE rank applies it to its own tokens ahead of the dispatch exchange
- * (assignment A of Sec. 3.1 with the locality-first rule of Sec. 4.3): in the layout of
- * probe_permute with the R ranks in the place of weight slots.  Expert e lists the ranks that
- * hold a copy of it, ascending; rep_rank = that rank (the "slot"); rep_weight = n[rs][e][r], the
- * tokens that originate on rs and are planned for the copy on r.  When no token of e was predicted
- * from this origin, an unforeseen one stays on rs if rs holds a copy and goes to e's home otherwise
- * (weight 1 there).  The replica lists are those of oracle_plan_for_rank (same rep_off).
+ * (assignment A of Sec. 3.1 with the locality-first rule of Sec. 4.3), in the layout of
+ * probe_permute.  A "slot" here is one (destination rank, expert) pair: every copy of every expert
+ * gets a slot of its own, numbered by destination rank first and expert second, so that permute
+ * groups the source's pairs by destination rank (the send order of the exchange) and, inside a
+ * rank, by expert.  Expert e lists its copies by ascending rank; rep_slot = the copy's slot;
+ * rep_weight = n[rs][e][r], the tokens that originate on rs and are planned for the copy on r.
+ * When no token of e was predicted from this origin, an unforeseen one stays on rs if rs holds a
+ * copy and goes to e's home otherwise (weight 1 there).  The replica lists are those of
+ * oracle_plan_for_rank (same rep_off).
+ *   rank_off    [R+1]  slots rank_off[r] .. rank_off[r+1]-1 are sent to rank r
+ *   slot_expert [rep_off[E]]  expert of each slot
  */
 int oracle_plan_dispatch(const int32_t* n, const int32_t* delta_in, int R, int E, int E_loc,
-                         int max_replicas, int rs, int32_t* rep_off, int32_t* rep_rank,
-                         int32_t* rep_weight) {
+                         int max_replicas, int rs, int32_t* rep_off, int32_t* rep_slot,
+                         int32_t* rep_weight, int32_t* rank_off, int32_t* slot_expert) {
   if (rs < 0 || rs >= R) return -1;
+  char* holds = (char*)calloc((size_t)E * R, 1); /* holds[e*R + r] */
+  if (!holds) return -2;
+  for (int e = 0; e < E; ++e) holds[(size_t)e * R + e / E_loc] = 1;
+  for (int r = 0; r < R; ++r)
+    for (int i = 0; i < max_replicas; ++i) {
+      int e = delta_in[(size_t)r * max_replicas + i];
+      if (e >= 0 && e < E) holds[(size_t)e * R + r] = 1;
+    }
+  /* slots: destination rank first, expert second */
+  int slot = 0;
+  for (int r = 0; r < R; ++r) {
+    rank_off[r] = slot;
+    for (int e = 0; e < E; ++e)
+      if (holds[(size_t)e * R + r]) slot_expert[slot++] = e;
+  }
+  rank_off[R] = slot;
   int pos = 0;
   for (int e = 0; e < E; ++e) {
     rep_off[e] = pos;
     int64_t planned = 0;
     int home_pos = pos, own_pos = -1;
     for (int r = 0; r < R; ++r) {
-      int here = (e / E_loc == r);
-      if (here) home_pos = pos;
-      for (int i = 0; i < max_replicas && !here; ++i)
-        if (delta_in[(size_t)r * max_replicas + i] == e) here = 1;
-      if (!here) continue;
+      if (!holds[(size_t)e * R + r]) continue;
+      if (r == e / E_loc) home_pos = pos;
       if (r == rs) own_pos = pos;
-      rep_rank[pos] = r;
+      int sl = rank_off[r];
+      for (int e2 = 0; e2 < e; ++e2) sl += holds[(size_t)e2 * R + r];
+      rep_slot[pos] = sl;
       rep_weight[pos] = n[IDX(rs, e, r)];
       planned += n[IDX(rs, e, r)];
       pos += 1;
@@ -306,6 +326,6 @@ int oracle_plan_dispatch(const int32_t* n, const int32_t* delta_in, int R, int E
     if (planned == 0) rep_weight[own_pos >= 0 ? own_pos : home_pos] = 1;
   }
   rep_off[E] = pos;
+  free(holds);
   return 0;
 }
-

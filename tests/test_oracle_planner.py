@@ -160,24 +160,27 @@ def test_plan_for_rank_layout(oracle):
 
 
 def test_plan_dispatch_hand_worked_and_ties_to_the_receiving_plan(oracle):
-    """The plan as a source rank applies it to its own tokens (ranks in the place of slots).
+    """The plan as a source rank applies it to its own tokens: one slot per (destination rank, expert copy).
     Hand-worked on the state after the first move of the three-rank example: expert 0 is held by ranks 0
-    (home) and 1 (copy); origin 2's 40 tokens of it are planned 17 on rank 0 and 23 on rank 1; its own expert 2
-    keeps its 10 tokens at home; it predicted nothing for expert 1, whose home is rank 1."""
+    (home) and 1 (copy), experts 1 and 2 by their homes.  Slots by destination rank, then expert:
+    rank 0: (e0) = slot 0;  rank 1: (e0) = 1, (e1) = 2;  rank 2: (e2) = 3.  Origin 2's 40 tokens of expert 0
+    are planned 17 on rank 0 and 23 on rank 1; its own expert 2 keeps its 10 tokens at home; it predicted
+    nothing for expert 1, whose home is rank 1."""
     nh = np.array([[20, 0, 0], [30, 10, 0], [40, 0, 10]], np.int32)
     r1 = oracle.plan_greedy(nh, 1, max_replicas=2, budget=2, k_max=1)
     d2 = oracle.plan_dispatch(r1["n"], r1["delta_in"], 1, rank=2)
     np.testing.assert_array_equal(d2["rep_off"], [0, 2, 3, 4])
-    np.testing.assert_array_equal(d2["rep_slot"], [0, 1, 1, 2])           # destination ranks
+    np.testing.assert_array_equal(d2["rep_slot"], [0, 1, 2, 3])
     np.testing.assert_array_equal(d2["rep_weight"], [17, 23, 1, 10])
-    assert d2["num_slots"] == 3
+    np.testing.assert_array_equal(d2["rank_off"], [0, 1, 3, 4])
+    np.testing.assert_array_equal(d2["slot_expert"], [0, 0, 1, 2])
     # origin 1 holds the copy: locality first, all 30 of its tokens of expert 0 stay on rank 1
     d1 = oracle.plan_dispatch(r1["n"], r1["delta_in"], 1, rank=1)
     np.testing.assert_array_equal(d1["rep_weight"], [0, 30, 10, 1])
-    np.testing.assert_array_equal(d1["rep_slot"], [0, 1, 1, 2])
-    # random cases: same replica lists as the receiving plan, the weights of all origins add up to the
-    # receiving plan's weights, every origin's weights add up to what it predicted, and an origin that holds
-    # a copy of an expert keeps its own tokens of it
+    np.testing.assert_array_equal(d1["rep_slot"], [0, 1, 2, 3])
+    # random cases: same replica lists as the receiving plan, slots unique and ordered by rank then expert,
+    # the weights of all origins add up to the receiving plan's weights, every origin's weights add up to what
+    # it predicted, and an origin that holds a copy of an expert keeps its own tokens of it
     for seed, R, E, E_loc in ((1, 4, 16, 4), (2, 8, 64, 8), (3, 5, 20, 4)):
         nh = _random_nhat(seed, R, E)
         r = oracle.plan_greedy(nh, E_loc, max_replicas=3, budget=2, k_max=16, n0=16, g_num=1, g_den=4)
@@ -187,9 +190,15 @@ def test_plan_dispatch_hand_worked_and_ties_to_the_receiving_plan(oracle):
         for rs in range(R):
             d = oracle.plan_dispatch(r["n"], r["delta_in"], E_loc, rank=rs)
             np.testing.assert_array_equal(d["rep_off"], recv["rep_off"])
+            used = int(d["rep_off"][E])
+            assert sorted(d["rep_slot"].tolist()) == list(range(used)) and d["rank_off"][R] == used
+            slot_rank = np.searchsorted(d["rank_off"], np.arange(used), side="right") - 1
+            for r_ in range(R):                                   # inside a rank, slots follow the expert order
+                assert (np.diff(d["slot_expert"][slot_rank == r_]) > 0).all()
             for e in range(E):
                 sl = slice(d["rep_off"][e], d["rep_off"][e + 1])
-                w, ranks = d["rep_weight"][sl], d["rep_slot"][sl]
+                w, ranks = d["rep_weight"][sl], slot_rank[d["rep_slot"][sl]]
+                assert (d["slot_expert"][d["rep_slot"][sl]] == e).all()
                 assert (np.diff(ranks) > 0).all() and (e // E_loc) in ranks
                 if nh[rs, e] > 0:
                     assert w.sum() == nh[rs, e]
