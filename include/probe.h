@@ -183,8 +183,11 @@ int probe_predict_topk_residual(const void* h_prev_bf16, const float* w_gate_nex
  * n_{e,r} > 0 only where P_{r,e} = 1).  Expert e owns replicas rep_off[e] .. rep_off[e+1]-1.
  * Replica i lives in local weight slot rep_slot[i] in [0,S), or on another GPU (-1), and
  * receives rep_weight[i] out of every P_e = sum of e's weights consecutive arrivals
- * (weighted round-robin in pair order; P_e >= 1, weights >= 0).  The struct itself is host
- * memory; the three arrays are device memory, int32.
+ * (weighted round-robin in pair order; P_e >= 1, weights >= 0).  A weight slot holds one copy of
+ * one expert: no slot id may appear twice in rep_slot (the rows of a slot are then the arrivals of
+ * one replica, which is what lets a pair's row be computed without atomics); a plan that breaks
+ * this gives unspecified rows for the slots concerned.  The struct itself is host memory; the
+ * three arrays are device memory, int32.
  */
 typedef struct {
   const int32_t* rep_off;    /* device [E+1] */
@@ -354,6 +357,27 @@ int probe_plan_greedy(const int32_t* n_hat, int R, int E, int E_loc, int rank,
                       int32_t* rep_weight, int32_t* slot_expert, int32_t* delta_in, int32_t* delta_out,
                       int32_t* moves, int64_t* stats, int32_t* n_assign, void* workspace,
                       size_t workspace_bytes, void* stream);
+
+/* The plan of probe_plan_greedy as the SOURCE rank applies it to its own tokens ahead of the dispatch
+ * exchange (assignment A of Sec. 3.1; locality first, Sec. 4.3), in the layout of probe_plan.  A slot
+ * here is one (destination rank, expert copy) pair, numbered by destination rank first and expert
+ * second; expert e lists its copies by ascending rank, rep_slot = the copy's slot, rep_weight =
+ * n_assign[rank][e][r], the tokens from this origin planned for the copy on r.  With no token of e
+ * predicted from this origin, an unforeseen one stays here if this rank holds a copy and goes to e's
+ * home otherwise (weight 1).  probe_permute with this plan (num_slots = E + R*max_replicas) groups this
+ * rank's pairs by destination rank and, inside a rank, by expert: slot_offsets[rank_off[r]] ..
+ * slot_offsets[rank_off[r+1]] are the rows of xp to send to rank r.
+ *   n_assign, delta_in  device, as written by probe_plan_greedy
+ *   rep_off      device, int32 [E+1]                    (out)
+ *   rep_slot     device, int32 [E + R*max_replicas]     (out)
+ *   rep_weight   device, int32 [E + R*max_replicas]     (out)
+ *   rank_off     device, int32 [R+1]                    (out) first slot of every destination rank
+ *   slot_expert  device, int32 [E + R*max_replicas]     (out) expert of each slot in use
+ * Limits as probe_plan_greedy.  No workspace.
+ */
+int probe_plan_dispatch(const int32_t* n_assign, const int32_t* delta_in, int R, int E, int E_loc,
+                        int max_replicas, int rank, int32_t* rep_off, int32_t* rep_slot,
+                        int32_t* rep_weight, int32_t* rank_off, int32_t* slot_expert, void* stream);
 
 /* ---------------------------------------------------------------------------- metrics ---
  *

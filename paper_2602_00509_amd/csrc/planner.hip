@@ -289,7 +289,106 @@ __global__ __launch_bounds__(256) void plan_greedy_kernel(const int32_t* __restr
   }
 }
 
+// The plan as source rank `rank` applies it to its own tokens: one slot per (destination rank, expert
+// copy), numbered by rank first and expert second.  One workgroup; thread e finds the ranks that hold
+// expert e (home + the replicas listed in delta_in); per rank, wave ballots and per-wave totals give the
+// number of lower experts held there (the slot inside the rank) and the rank's slot count; a block scan
+// of the copies per expert gives rep_off.
+__global__ __launch_bounds__(256) void plan_dispatch_kernel(const int32_t* __restrict__ n_assign,
+                                                            const int32_t* __restrict__ delta_in, int R, int E,
+                                                            int E_loc, int max_replicas, int rank,
+                                                            int32_t* __restrict__ rep_off,
+                                                            int32_t* __restrict__ rep_slot,
+                                                            int32_t* __restrict__ rep_weight,
+                                                            int32_t* __restrict__ rank_off,
+                                                            int32_t* __restrict__ slot_expert) {
+  __shared__ int32_t wave_tot[4];
+  __shared__ int32_t wave_cnt[kPlanMaxRanks][4];
+  __shared__ int32_t r_off[kPlanMaxRanks + 1];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, e = tid;
+  uint32_t hm = 0;
+  if (e < E) {
+    hm = 1u << (e / E_loc);
+    for (int r = 0; r < R; ++r)
+      for (int i = 0; i < max_replicas; ++i)
+        if (delta_in[r * max_replicas + i] == e) hm |= 1u << r;
+  }
+  const uint64_t lower = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+  int within[kPlanMaxRanks];  // experts below e, in this wave, held by rank r
+#pragma unroll
+  for (int r = 0; r < kPlanMaxRanks; ++r) {
+    const uint64_t m = __ballot((hm >> r) & 1u);
+    within[r] = __popcll(m & lower);
+    if (lane == 0) wave_cnt[r][wv] = __popcll(m);
+  }
+  const int cnt = __popc(hm);
+  int incl = cnt;
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    int o = __shfl_up(incl, d, kWave);
+    if (lane >= d) incl += o;
+  }
+  if (lane == kWave - 1) wave_tot[wv] = incl;
+  __syncthreads();
+  if (tid == 0) {
+    int run = 0;
+    for (int r = 0; r < R; ++r) {
+      r_off[r] = run;
+      rank_off[r] = run;
+      run += wave_cnt[r][0] + wave_cnt[r][1] + wave_cnt[r][2] + wave_cnt[r][3];
+    }
+    r_off[R] = run;
+    rank_off[R] = run;
+  }
+  __syncthreads();
+  int pos = incl - cnt;
+  for (int i = 0; i < wv; ++i) pos += wave_tot[i];
+  if (e < E) {
+    const int home = e / E_loc;
+    rep_off[e] = pos;
+    long long planned = 0;
+    int home_pos = pos, own_pos = -1;
+#pragma unroll
+    for (int r = 0; r < kPlanMaxRanks; ++r) {
+      if (r < R && ((hm >> r) & 1u)) {
+        int slot = r_off[r] + within[r];
+        for (int i = 0; i < wv; ++i) slot += wave_cnt[r][i];
+        const int w = n_assign[(static_cast<long>(rank) * E + e) * R + r];
+        if (r == home) home_pos = pos;
+        if (r == rank) own_pos = pos;
+        rep_slot[pos] = slot;
+        rep_weight[pos] = w;
+        slot_expert[slot] = e;
+        planned += w;
+        pos += 1;
+      }
+    }
+    // nothing predicted from this origin: an unforeseen token stays here if a copy is here, else goes home
+    if (planned == 0) rep_weight[own_pos >= 0 ? own_pos : home_pos] = 1;
+    if (e == E - 1) rep_off[E] = pos;
+  }
+}
+
 }  // namespace probe
+
+extern "C" int probe_plan_dispatch(const int32_t* n_assign, const int32_t* delta_in, int R, int E, int E_loc,
+                                   int max_replicas, int rank, int32_t* rep_off, int32_t* rep_slot,
+                                   int32_t* rep_weight, int32_t* rank_off, int32_t* slot_expert, void* stream) {
+  using namespace probe;
+  PROBE_REQUIRE(R >= 1 && E >= 1 && E_loc >= 1 && static_cast<long>(E_loc) * R >= E && rank >= 0 && rank < R &&
+                    max_replicas >= 0,
+                PROBE_EINVAL, "probe_plan_dispatch: bad dims R=%d E=%d E_loc=%d rank=%d max_replicas=%d", R, E, E_loc,
+                rank, max_replicas);
+  PROBE_REQUIRE(R <= kPlanMaxRanks && E <= PROBE_MAX_EXPERTS && max_replicas <= kPlanMaxReplicas, PROBE_EUNSUPPORTED,
+                "probe_plan_dispatch: needs R <= %d, E <= %d, max_replicas <= %d", kPlanMaxRanks, PROBE_MAX_EXPERTS,
+                kPlanMaxReplicas);
+  PROBE_REQUIRE(n_assign && (delta_in || max_replicas == 0) && rep_off && rep_slot && rep_weight && rank_off &&
+                    slot_expert,
+                PROBE_EINVAL, "probe_plan_dispatch: null pointer");
+  hipLaunchKernelGGL(plan_dispatch_kernel, dim3(1), dim3(256), 0, static_cast<hipStream_t>(stream), n_assign,
+                     delta_in, R, E, E_loc, max_replicas, rank, rep_off, rep_slot, rep_weight, rank_off, slot_expert);
+  return check_launch("probe_plan_dispatch");
+}
 
 extern "C" size_t probe_plan_greedy_workspace_bytes(int R, int E) {
   if (R <= 0 || E <= 0) return 0;

@@ -89,6 +89,8 @@ def lib():
         L.probe_plan_greedy.restype = C.c_int
         L.probe_plan_greedy.argtypes = ([C.c_void_p] + [C.c_int] * 4 + [C.POINTER(_PlannerParams)] +
                                         [C.c_void_p] * 10 + [C.c_size_t, C.c_void_p])
+        L.probe_plan_dispatch.restype = C.c_int
+        L.probe_plan_dispatch.argtypes = [C.c_void_p] * 2 + [C.c_int] * 5 + [C.c_void_p] * 6
         L.probe_predictor_metrics.restype = C.c_int
         L.probe_predictor_metrics.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int,
                                               C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -334,6 +336,30 @@ def plan_greedy(n_hat, E_loc, rank=0, max_replicas=3, budget=3, k_max=16, eps=0,
                                  _stream(stream))
     _check(rc)
     out["plan"] = Plan(out["rep_off"], out["rep_slot"], out["rep_weight"], E_loc + max_replicas, dev)
+    return out
+
+
+def plan_dispatch(n_assign, delta_in, E_loc, rank, *, stream=None):
+    """probe_plan_dispatch: the plan as source rank ``rank`` applies it to its own tokens; one slot per
+    (destination rank, expert copy), ranks first.
+
+    n_assign int32 [R,E,R] and delta_in int32 [R,max_replicas] as written by plan_greedy(want_assignment=True).
+    Returns dict(plan=Plan with num_slots = E + R*max_replicas, rep_off, rep_slot, rep_weight, rank_off, slot_expert)."""
+    R, E, _ = n_assign.shape
+    max_replicas = delta_in.shape[1]
+    _want(n_assign, torch.int32, (R, E, R), "n_assign")
+    _want(delta_in, torch.int32, (R, max_replicas), "delta_in")
+    dev = n_assign.device
+    i32 = dict(dtype=torch.int32, device=dev)
+    cap = E + R * max_replicas
+    out = dict(rep_off=torch.empty((E + 1,), **i32), rep_slot=torch.empty((cap,), **i32),
+               rep_weight=torch.empty((cap,), **i32), rank_off=torch.empty((R + 1,), **i32),
+               slot_expert=torch.full((cap,), -1, **i32))
+    rc = lib().probe_plan_dispatch(_ptr(n_assign), _ptr(delta_in), R, E, int(E_loc), max_replicas, int(rank),
+                                   _ptr(out["rep_off"]), _ptr(out["rep_slot"]), _ptr(out["rep_weight"]),
+                                   _ptr(out["rank_off"]), _ptr(out["slot_expert"]), _stream(stream))
+    _check(rc)
+    out["plan"] = Plan(out["rep_off"], out["rep_slot"], out["rep_weight"], cap, dev)
     return out
 
 

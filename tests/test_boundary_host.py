@@ -110,6 +110,9 @@ def test_bad_arguments_are_rejected_without_a_launch(L):
     assert pg(8, 64, 8, 0, pp, nh=None) == -1
     assert pg(8, 64, 8, 0, pp, ws=C.c_size_t(64)) == -4 and "workspace" in err()
     assert L.probe_plan_greedy_workspace_bytes(8, 64) >= 64 * 8 * 8 * 4
+    pd = lambda R, E, El, mr, rank, na=fake: L.probe_plan_dispatch(na, fake, R, E, El, mr, rank, fake, fake, fake, fake, fake, None)
+    assert pd(8, 64, 8, 3, 8) == -1 and pd(8, 64, 4, 3, 0) == -1 and pd(8, 64, 8, 3, 0, na=None) == -1
+    assert pd(32, 64, 2, 3, 0) == -2 and pd(8, 64, 8, 9, 0) == -2
     # permute
     plan = _Plan(0x1000, 0x1000, 0x1000, 4)
     args = lambda **kw: None

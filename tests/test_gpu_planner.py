@@ -117,3 +117,61 @@ def test_predict_plan_permute_stays_on_the_device(oracle, probe, G):
     for s in range(E_loc, E_loc + 3):
         if se[s] >= 0:
             assert o_p["slot_counts"][s] > 0
+
+
+@pytest.mark.parametrize("seed,R,E,E_loc", [(1, 4, 16, 4), (2, 8, 64, 8), (3, 8, 256, 32), (5, 16, 128, 8), (8, 2, 3, 2)])
+def test_dispatch_plan_matches_oracle(oracle, probe, seed, R, E, E_loc):
+    """probe_plan_dispatch for every source rank, bit for bit against the oracle."""
+    nh = _random_nhat(seed, R, E)
+    kw = dict(max_replicas=3, budget=2, k_max=16, n0=16, g_num=1, g_den=4)
+    o = oracle.plan_greedy(nh, E_loc, **kw)
+    g = probe.plan_greedy(torch.from_numpy(nh).cuda(), E_loc, rank=0, want_assignment=True, **kw)
+    for rs in range(R):
+        d = probe.plan_dispatch(g["n"], g["delta_in"], E_loc, rs)
+        torch.cuda.synchronize()
+        od = oracle.plan_dispatch(o["n"], o["delta_in"], E_loc, rs)
+        used = int(od["rep_off"][E])
+        np.testing.assert_array_equal(d["rep_off"].cpu().numpy(), od["rep_off"])
+        np.testing.assert_array_equal(d["rep_slot"].cpu().numpy()[:used], od["rep_slot"])
+        np.testing.assert_array_equal(d["rep_weight"].cpu().numpy()[:used], od["rep_weight"])
+        np.testing.assert_array_equal(d["rank_off"].cpu().numpy(), od["rank_off"])
+        np.testing.assert_array_equal(d["slot_expert"].cpu().numpy()[:used], od["slot_expert"])
+
+
+def test_source_side_grouping_by_destination_rank(oracle, probe, G):
+    """One source rank's own tokens: route -> counts of every source rank -> plan -> dispatch plan -> permute.
+    When the prediction is the routing itself, the send counts are exactly the planned ones, tokens of an expert
+    this rank holds stay here, rows are grouped by destination rank and inside a rank by expert, and everything
+    matches the oracle."""
+    cfg = wl.small_config(T=1024, H=64, E=32, k=4, F=64, E_loc=4, n_rep=0, zipf_s=1.3, ep=8, cid=97)
+    R, E, E_loc, k, me = 8, cfg.E, 4, cfg.k, 3
+    L = G.Layer(cfg, 0)
+    route = probe.route_topk(L.d_x, L.d_wg, L.d_bias, L.tpg, k, True)
+    mine = route["counts"].cpu().numpy().astype(np.int32)
+    nh = np.stack([mine if r == me else _random_nhat(40 + r, 1, E, scale=100)[0] for r in range(R)]).astype(np.int32)
+    kw = dict(max_replicas=3, budget=3, k_max=16, n0=16, g_num=1, g_den=2)
+    g = probe.plan_greedy(torch.from_numpy(nh).cuda(), E_loc, rank=me, want_assignment=True, **kw)
+    d = probe.plan_dispatch(g["n"], g["delta_in"], E_loc, me)
+    perm = probe.permute(route["idx"], d["plan"], L.d_x)
+    torch.cuda.synchronize()
+    o = oracle.plan_greedy(nh, E_loc, **kw)
+    assert o["n_moves"] >= 1
+    od = oracle.plan_dispatch(o["n"], o["delta_in"], E_loc, me)
+    idx = route["idx"].cpu().numpy()
+    o_p = oracle.permute(idx, od["rep_off"], od["rep_slot"], od["rep_weight"], od["num_slots"], L.x)
+    for key in ("slot_counts", "slot_offsets", "pair_row"):
+        np.testing.assert_array_equal(perm[key].cpu().numpy(), o_p[key])
+    assert int(perm["n_local"].item()) == cfg.T * k                     # every pair has a destination
+    np.testing.assert_array_equal(G.bits_of(perm["xp"]), o_p["xp"])
+    # send counts per destination rank = what the planner assigned to this origin
+    so, ro = o_p["slot_offsets"], od["rank_off"]
+    np.testing.assert_array_equal(so[ro[1:]] - so[ro[:-1]], o["n"][me].sum(0))
+    # rows of a slot carry that slot's expert; locality first: pairs of an expert that this rank holds stay here
+    used = int(od["rep_off"][E])
+    row_slot = np.searchsorted(so[:used + 1], np.arange(cfg.T * k), side="right") - 1
+    row_expert = idx.ravel()[o_p["row_pair"]]
+    np.testing.assert_array_equal(od["slot_expert"][row_slot], row_expert)
+    dest = np.searchsorted(ro, row_slot, side="right") - 1
+    held = set(range(me * E_loc, (me + 1) * E_loc)) | {int(e) for e in o["delta_in"][me] if e >= 0}
+    for e in held:
+        assert (dest[row_expert == e] == me).all()
