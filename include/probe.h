@@ -20,8 +20,9 @@
  * Variants of these: probe_route_predict_topk (router and next layer's predictor in one pass over
  * the hidden states), probe_route_grouped (a model's group-limited gate in place of the plain
  * top-k), probe_grouped_ffn_gather (activation rows gathered on load, no permuted copy),
- * probe_combine_shared (adds a shared expert's output), and probe_predictor_metrics (top-k
- * accuracy and distillation cross-entropy of a predictor, evaluation only).
+ * probe_combine_shared (adds a shared expert's output), probe_plan_dispatch (the plan as the source
+ * rank applies it to its own tokens ahead of the dispatch exchange), and probe_predictor_metrics
+ * (top-k accuracy and distillation cross-entropy of a predictor, evaluation only).
  *
  * Conventions for every call
  *   - Every pointer marked "device" is caller-owned device memory; the library never
