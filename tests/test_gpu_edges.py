@@ -337,3 +337,73 @@ def test_more_tokens_than_one_pass_of_any_grid(oracle, probe, G):
     print("case many tokens", flush=True)
     res = G.run_layer_parity(oracle, probe, cfg, batch=0, route_sample=None, ffn_sample=64, seed=96)
     assert res["n_local"] > 100000
+
+
+def test_graph_replay_of_the_variant_entry_points(oracle, probe, G):
+    """The planner, the dispatch plan, the group-limited gate, permute without the row copy, the FFN with rows
+    gathered on load and the combine with a shared expert record into one HIP graph; every replay, with eager
+    work in between, reproduces the eager results bit for bit."""
+    print("case graph replay, variants", flush=True)
+    cfg = wl.small_config(T=384, H=128, E=32, k=4, F=128, E_loc=8, n_rep=0, ep=4, chunk=0, cid=98)
+    T, H, E, k, F, R, E_loc = cfg.T, cfg.H, cfg.E, cfg.k, cfg.F, 4, 8
+    L = G.Layer(cfg, 0)
+    rng = np.random.default_rng(98)
+    nh = torch.from_numpy(rng.poisson(60, size=(R, E)).astype(np.int32)).cuda()
+    nh[:, 3] *= 6                                                  # a hot expert, so that the planner moves something
+    sb = torch.from_numpy((rng.standard_normal(E) * 0.05).astype(np.float32)).cuda()
+    kw = dict(max_replicas=2, budget=2, k_max=8, n0=16, g_num=1, g_den=2)
+    S = E_loc + 2
+    ws = wl.expert_weights_many(cfg, list(range(E)))
+    d_w = [(G.dev_bf16(a), G.dev_bf16(b)) for a, b in ws]
+    shared_tab = probe.WeightTable([d_w[0][0]], [d_w[0][1]])
+    so_shared = torch.tensor([0, T], dtype=torch.int32, device="cuda")
+    res = {}
+
+    def step():
+        g = probe.plan_greedy(nh, E_loc, rank=0, want_assignment=True, **kw)
+        d = probe.plan_dispatch(g["n"], g["delta_in"], E_loc, 0)
+        r = probe.route_grouped(L.d_x, L.d_wg, None, None, sb, scoring="sigmoid", n_group=4, topk_group=2, group_top=2,
+                                k=k, renormalize=True, routed_scale=2.5)
+        p = probe.permute(r["idx"], g["plan"], L.d_x, copy_rows=False)
+        res.update(g=g, d=d, r=r, p=p)
+        return g, d, r, p
+
+    # the weight table follows the planner's slot_expert, which is fixed for a fixed n_hat: build it once, eagerly
+    g0, _, _, _ = step()
+    torch.cuda.synchronize()
+    se = g0["slot_expert"].cpu().numpy()
+    assert (se[E_loc:] >= 0).any()
+    tab = probe.WeightTable([d_w[max(int(e), 0)][0] for e in se], [d_w[max(int(e), 0)][1] for e in se])
+
+    def full():
+        g, d, r, p = step()
+        y = probe.grouped_ffn_gather(L.d_x, p["row_pair"], k, p["slot_offsets"], tab)
+        shared = probe.grouped_ffn(L.d_x, so_shared, shared_tab)
+        y0 = torch.where(torch.arange(y.shape[0], device="cuda")[:, None] < p["n_local"], y, torch.zeros_like(y))
+        out = probe.combine_shared(y0, p["pair_row"], r["w"], shared, 1.0)
+        res.update(out=out, y0=y0)
+
+    full()
+    torch.cuda.synchronize()
+    ref = dict(out=res["out"].clone(), idx=res["r"]["idx"].clone(), rows=res["p"]["pair_row"].clone(),
+               rep_w=res["g"]["rep_weight"].clone(), dslot=res["d"]["rep_slot"].clone(), y0=res["y0"].clone())
+    assert (ref["rows"] >= 0).any() and ref["out"].float().abs().sum() > 0
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            full()
+    torch.cuda.synchronize()
+    cap = dict(out=res["out"], idx=res["r"]["idx"], rows=res["p"]["pair_row"], rep_w=res["g"]["rep_weight"],
+               dslot=res["d"]["rep_slot"], y0=res["y0"])
+    used = int(res["g"]["rep_off"][-1])
+    for i in range(3):
+        for t in cap.values():
+            t.zero_()                        # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(cap["idx"], ref["idx"]) and torch.equal(cap["rows"], ref["rows"]), i
+        assert torch.equal(cap["rep_w"][:used], ref["rep_w"][:used]) and torch.equal(cap["dslot"][:used], ref["dslot"][:used]), i
+        assert torch.equal(cap["y0"], ref["y0"]) and torch.equal(cap["out"], ref["out"]), i
