@@ -54,6 +54,10 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="record each batch's step into a HIP graph and time replays (stage times still come from "
                          "an eager pass)")
+    ap.add_argument("--unpacked-gate", action="store_true",
+                    help="hand the router and the predictor the fp32 gate matrices, which they split into bf16 planes "
+                         "on every call (default: planes made once by probe_pack_gate, untimed set-up whose cost is "
+                         "reported as gate_pack_us)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -108,6 +112,21 @@ def main():
     ws_route = torch.empty(probe.route_topk_workspace_bytes(T, H, E, k), dtype=torch.uint8, device=dev)
     ws_fused = (torch.empty(probe.route_predict_topk_workspace_bytes(T, H, E, k), dtype=torch.uint8, device=dev)
                 if args.fused_route_predict else None)
+    # the gates as the calls take them: bf16 planes packed once (the router's weights are frozen while serving),
+    # or the fp32 matrices themselves
+    g_route, g_pred, g_fused, g_fused_next, pack_us = d_wg, d_wg_next, d_wg, d_wg_next, None
+    if not args.unpacked_gate:
+        probe.PackedGate(d_wg)                    # first call: module load
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        g_route = probe.PackedGate(d_wg)
+        e1.record()
+        torch.cuda.synchronize()
+        pack_us = e0.elapsed_time(e1) * 1e3
+        g_pred = probe.PackedGate(d_wg_next)
+        if args.fused_route_predict:
+            g_fused, g_fused_next = probe.PackedGate(d_wg, d_wg_next), None
     D = args.residual_width
     if D:
         rng = np.random.default_rng(1000 + cfg.cid)
@@ -152,17 +171,17 @@ def main():
                 ev[i].record()
         mark(0)
         if args.fused_route_predict:
-            probe.route_predict_topk(d_xs[b], d_wg, d_bias[b], d_wg_next, d_bias_next[b], tpg, k, True, out=r_out,
-                                     pred_out=p_out_pred, workspace=ws_fused)
+            probe.route_predict_topk(d_xs[b], g_fused, d_bias[b], g_fused_next, d_bias_next[b], tpg, k, True,
+                                     out=r_out, pred_out=p_out_pred, workspace=ws_fused)
             mark(1)
         elif D:
             probe.predict_topk_residual(d_xs[b], d_wg_next, d_bias_next[b], tpg, d_w1, d_w2, k, True, out=p_out_pred,
                                         workspace=ws_pred)
         else:
-            probe.predict_topk(d_xs[b], d_wg_next, d_bias_next[b], tpg, k, True, out=p_out_pred, workspace=ws_route)
+            probe.predict_topk(d_xs[b], g_pred, d_bias_next[b], tpg, k, True, out=p_out_pred, workspace=ws_route)
         if not args.fused_route_predict:
             mark(1)
-            probe.route_topk(d_xs[b], d_wg, d_bias[b], tpg, k, True, out=r_out, workspace=ws_route)
+            probe.route_topk(d_xs[b], g_route, d_bias[b], tpg, k, True, out=r_out, workspace=ws_route)
         mark(2)
         if args.gather_on_load:
             probe.permute(r_out["idx"], d_plans[b], d_xs[b], out=perm_lean, workspace=ws_perm, copy_rows=False)
@@ -246,6 +265,8 @@ def main():
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic", "launch": "hip_graph_replay" if args.graph else "eager",
+        "gate": "fp32 matrices, split per call" if args.unpacked_gate else "bf16 planes packed once (probe_pack_gate)",
+        "gate_pack_us": pack_us,
         "config": {"workload": "cfg%d %s: T=%d H=%d E=%d top-%d F=%d, %d native + %d replica slots, Zipf s=%.1f, "
                                "%d rotating batches" % (cfg.cid, cfg.name, T, H, E, k, F, cfg.E_loc, cfg.n_rep,
                                                         cfg.zipf_s, nb),

@@ -17,7 +17,8 @@
  *   probe_combine       gate-weighted sum of a token's expert outputs (local part of the
  *                       combine step)
  *
- * Variants of these: probe_route_predict_topk (router and next layer's predictor in one pass over
+ * Variants of these: probe_pack_gate and the *_packed router / predictor calls (the gate's bf16 planes
+ * made once instead of per call), probe_route_predict_topk (router and next layer's predictor in one pass over
  * the hidden states), probe_route_grouped (a model's group-limited gate in place of the plain
  * top-k), probe_grouped_ffn_gather (activation rows gathered on load, no permuted copy),
  * probe_combine_shared (adds a shared expert's output), probe_plan_dispatch (the plan as the source
@@ -307,6 +308,58 @@ int probe_route_predict_topk(const void* x_bf16, const float* w_gate, const floa
                              int32_t* topk_idx, float* topk_w, float* probs, int32_t* expert_counts,
                              int32_t* pred_idx, float* pred_w, float* pred_probs, int32_t* pred_counts,
                              void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------ packed gate ---
+ *
+ * The router's weights are frozen while serving (Sec. 4.2: the predictor clones (W_L, b_L)), so the
+ * split of the fp32 gate into the three bf16 planes that the matrix cores consume can be done once
+ * instead of inside every call.  probe_pack_gate writes them; the *_packed entry points take the planes
+ * in place of the fp32 matrix and are otherwise the calls of the same name: same arithmetic, same
+ * results bit for bit, a workspace smaller by the planes.
+ *
+ *   packed      device, bf16 [3][stack_rows][H], probe_pack_gate_bytes(H, stack_rows) bytes; plane p holds
+ *               for every weight the round-to-nearest bf16 of what planes 0..p-1 left of it
+ *   stack_rows  rows per plane; E for a single gate.  probe_route_predict_topk_packed takes one stack of
+ *               2E rows: this layer's gate packed at row_offset 0, the next layer's at row_offset E
+ *   row_offset  first row of this gate inside each plane
+ * Limits: H % 8 == 0.  The planes are read-only afterwards and may be shared by any number of calls.
+ */
+size_t probe_pack_gate_bytes(int H, int stack_rows);
+
+int probe_pack_gate(const float* w_gate, int H, int E, int stack_rows, int row_offset, void* packed,
+                    void* stream);
+
+size_t probe_route_topk_packed_workspace_bytes(int T, int H, int E, int k);
+
+int probe_route_topk_packed(const void* x_bf16, const void* packed_gate, const float* bias,
+                            int bias_groups, int tokens_per_group, int T, int H, int E, int k,
+                            int renormalize, int32_t* topk_idx, float* topk_w, float* probs,
+                            int32_t* expert_counts, void* workspace, size_t workspace_bytes,
+                            void* stream);
+
+/* workspace: probe_route_topk_packed_workspace_bytes */
+int probe_predict_topk_packed(const void* h_prev_bf16, const void* packed_gate_next,
+                              const float* bias_next, int bias_groups, int tokens_per_group, int T,
+                              int H, int E, int k, int renormalize, int32_t* pred_idx, float* pred_w,
+                              float* probs, int32_t* pred_counts, void* workspace,
+                              size_t workspace_bytes, void* stream);
+
+/* workspace: probe_route_topk_packed_workspace_bytes */
+int probe_route_grouped_packed(const void* x_bf16, const void* packed_gate, const float* bias,
+                               int bias_groups, int tokens_per_group, const float* select_bias,
+                               const probe_gating* gating, int T, int H, int E, int k,
+                               int32_t* topk_idx, float* topk_w, float* scores, int32_t* expert_counts,
+                               void* workspace, size_t workspace_bytes, void* stream);
+
+size_t probe_route_predict_topk_packed_workspace_bytes(int T, int H, int E, int k);
+
+int probe_route_predict_topk_packed(const void* x_bf16, const void* packed_stack, const float* bias,
+                                    const float* bias_next, int bias_groups, int tokens_per_group,
+                                    int T, int H, int E, int k, int renormalize, int32_t* topk_idx,
+                                    float* topk_w, float* probs, int32_t* expert_counts,
+                                    int32_t* pred_idx, float* pred_w, float* pred_probs,
+                                    int32_t* pred_counts, void* workspace, size_t workspace_bytes,
+                                    void* stream);
 
 /* ---------------------------------------------------------------------------- planner ---
  *

@@ -66,14 +66,19 @@ static_assert(sizeof(TileEntry) == 32, "one 32-byte record per tile");
 constexpr bool kInterleave = true;
 
 struct SlotCut {
-  int n320, n256, tail;  // tail = height of the one short tile (64, 128 or 192), 0 if there is none
-  __device__ __forceinline__ int tiles() const { return n320 + n256 + (tail ? 1 : 0); }
+  int n320, n256, n64, tail;  // tail = height of the one short tile (64, 128 or 192), 0 if there is none
+  __device__ __forceinline__ int tiles() const { return n320 + n256 + n64 + (tail ? 1 : 0); }
 };
 
-__device__ __forceinline__ SlotCut cut_slot(int m) {
-  SlotCut c = {0, 0, 0};
+// skinny = the decode schedule: every tile is 64 rows high (see ffn_gemm1_skinny_kernel)
+__device__ __forceinline__ SlotCut cut_slot(int m, bool skinny) {
+  SlotCut c = {0, 0, 0, 0};
   const int u = (m + 63) >> 6;
   if (u == 0) return c;
+  if (skinny) {
+    c.n64 = u;
+    return c;
+  }
   if (u <= 3) {
     c.tail = 64 * u;
     return c;
@@ -93,7 +98,7 @@ __device__ __forceinline__ SlotCut cut_slot(int m) {
 __global__ __launch_bounds__(256) void ffn_schedule_kernel(const int32_t* __restrict__ slot_offsets,
                                                            const void* const* __restrict__ w13_ptrs,
                                                            const void* const* __restrict__ w2_ptrs,
-                                                           int S, int max_tiles,
+                                                           int S, int max_tiles, int skinny,
                                                            int32_t* __restrict__ table) {
   __shared__ int32_t rows_of[PROBE_MAX_SLOTS];
   __shared__ int32_t first_of[PROBE_MAX_SLOTS];
@@ -134,7 +139,7 @@ __global__ __launch_bounds__(256) void ffn_schedule_kernel(const int32_t* __rest
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int p = tid * 4 + i;
-    v[i] = p < S ? cut_slot(rows_of[slot_at[p]]).tiles() : 0;
+    v[i] = p < S ? cut_slot(rows_of[slot_at[p]], skinny != 0).tiles() : 0;
     local += v[i];
   }
   int incl = local;
@@ -177,7 +182,7 @@ __global__ __launch_bounds__(256) void ffn_schedule_kernel(const int32_t* __rest
       if (start[mid] <= t) lo = mid; else hi = mid;
     }
     const int slot = slot_at[lo], first = first_of[slot];
-    const SlotCut c = cut_slot(rows_of[slot]);
+    const SlotCut c = cut_slot(rows_of[slot], skinny != 0);
     int i = t - start[lo], row0 = first, height;
     if (i < c.n320) {
       row0 += i * 320;
@@ -185,8 +190,11 @@ __global__ __launch_bounds__(256) void ffn_schedule_kernel(const int32_t* __rest
     } else if ((i -= c.n320) < c.n256) {
       row0 += c.n320 * 320 + i * 256;
       height = 256;
+    } else if ((i -= c.n256) < c.n64) {
+      row0 += c.n320 * 320 + c.n256 * 256 + i * 64;
+      height = 64;
     } else {
-      row0 += c.n320 * 320 + c.n256 * 256;
+      row0 += c.n320 * 320 + c.n256 * 256 + c.n64 * 64;
       height = c.tail;
     }
     TileEntry e;
@@ -200,12 +208,12 @@ __global__ __launch_bounds__(256) void ffn_schedule_kernel(const int32_t* __rest
   }
 }
 
-template <int MI>
-__device__ __forceinline__ void zero_acc(f32x16 (&acc)[MI][2]) {
+template <int MI, int NI>
+__device__ __forceinline__ void zero_acc(f32x16 (&acc)[MI][NI]) {
 #pragma unroll
   for (int i = 0; i < MI; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < NI; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 }
@@ -246,11 +254,14 @@ struct RowSource {
   int k, n_tokens;
 };
 
-template <int MI, bool GATHER>
+// NI = 32-row weight fragments per wave: 2 = a column block of 128 h columns (128 gate + 128 up weight
+// rows per workgroup), 1 = 64 h columns (the skinny tiles of the decode schedule).  NST = LDS stages.
+template <int MI, bool GATHER, int NI = 2, int NST = (MI >= 3 ? 2 : 3)>
 __device__ __forceinline__ void gemm1_tile(const RowSource& src, const bf16_t* __restrict__ w13,
                                            int row0, int rows, int n0, int H, int F,
                                            bf16_t* __restrict__ hbuf, u32x4* smem) {
   // rows = valid rows from row0 to the end of the slot (may exceed the tile height)
+  constexpr int HALF = 16 * NI;  // h columns per wave; its 32*NI weight rows are HALF gate rows, then the HALF up rows
   const int lane = threadIdx.x & 63;
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wv / 4, wn = wv % 4;
@@ -258,7 +269,7 @@ __device__ __forceinline__ void gemm1_tile(const RowSource& src, const bf16_t* _
       GATHER ? make_rsrc(src.base, static_cast<size_t>(src.n_tokens) * H * 2)
              : make_rsrc(src.base + static_cast<size_t>(row0) * H, static_cast<size_t>(rows) * H * 2);
   __amdgpu_buffer_rsrc_t rB = make_rsrc(w13, static_cast<size_t>(2) * F * H * 2);
-  int voff[MI + 4];
+  int voff[MI + 2 * NI];
   dma_offsets<MI>(wv, lane, H * 2,
                   [&](int r) {
                     const int rr = min(r, rows - 1);
@@ -267,17 +278,17 @@ __device__ __forceinline__ void gemm1_tile(const RowSource& src, const bf16_t* _
                     return min(max(pair, 0) / src.k, src.n_tokens - 1);
                   },
                   voff);
-  // weight tile row j: wave column block q = j / 64; inside it 32 gate rows, then the 32 up rows
-  dma_offsets<4>(wv, lane, H * 2,
-                 [&](int j) {
-                   int q = j >> 6, r = j & 63;
-                   int f = min(n0 + 32 * q + (r & 31), F - 1);  // columns past F are masked at the store
-                   return (r < 32) ? f : F + f;
-                 },
-                 voff + MI);
-  f32x16 acc[MI][2];
-  zero_acc<MI>(acc);
-  gemm_mainloop<MI, 2, 1, (MI >= 3 ? 2 : 3), true>(rA, rB, voff, 0, H, smem, wv, lane, acc);
+  // weight tile row j: wave column block q = j / (2 HALF); inside it HALF gate rows, then the HALF up rows
+  dma_offsets<2 * NI>(wv, lane, H * 2,
+                      [&](int j) {
+                        int q = j / (2 * HALF), r = j % (2 * HALF);
+                        int f = min(n0 + HALF * q + (r % HALF), F - 1);  // columns past F are masked at the store
+                        return (r < HALF) ? f : F + f;
+                      },
+                      voff + MI);
+  f32x16 acc[MI][NI];
+  zero_acc<MI, NI>(acc);
+  gemm_mainloop<MI, NI, 1, NST, true>(rA, rB, voff, 0, H, smem, wv, lane, acc);
 
   // Accumulator registers 8g .. 8g+7 of a lane are eight consecutive output columns of one output
   // row (see gemm_mainloop, PERM): one 16-byte store each.  The stores go through a buffer
@@ -286,17 +297,19 @@ __device__ __forceinline__ void gemm1_tile(const RowSource& src, const bf16_t* _
   const int valid = min(rows, 64 * MI);
   __amdgpu_buffer_rsrc_t rH = make_rsrc(hbuf + static_cast<size_t>(row0) * F, static_cast<size_t>(valid) * F * 2);
   const int row_in = 32 * MI * wm + (lane & 31);
-  const int cbase = n0 + 32 * wn + 8 * (lane >> 5);
+  const int cbase = n0 + HALF * wn + 8 * (lane >> 5);
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi) {
     const int off = ((row_in + 32 * mi) * F + cbase) * 2;
 #pragma unroll
-    for (int g = 0; g < 2; ++g) {
+    for (int g = 0; g < NI; ++g) {
       if (cbase + 16 * g < F) {  // F % 8 == 0: an 8-column group is in or out as a whole
         float hv[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          float gt = acc[mi][0][8 * g + e], up = acc[mi][1][8 * g + e];
+          // NI = 2: fragment 0 holds the gate rows, fragment 1 the up rows; NI = 1: registers 0..7 / 8..15
+          float gt = NI == 2 ? acc[mi][0][8 * g + e] : acc[mi][0][e];
+          float up = NI == 2 ? acc[mi][NI - 1][8 * g + e] : acc[mi][0][8 + e];
           hv[e] = gt / (1.f + __expf(-gt)) * up;
         }
         u32x4 pk;
@@ -336,7 +349,7 @@ __global__ __launch_bounds__(512, 2) void ffn_gemm1_kernel(RowSource src, const 
 }
 
 // ---- 2. gemm2 -------------------------------------------------------------------------
-template <int MI>
+template <int MI, int NI = 2, int NST = (MI >= 3 ? 2 : 3)>
 __device__ __forceinline__ void gemm2_tile(const bf16_t* __restrict__ hbuf, const bf16_t* __restrict__ w2,
                                            int row0, int rows, int n0, int H, int F,
                                            bf16_t* __restrict__ y, u32x4* smem) {
@@ -345,12 +358,12 @@ __device__ __forceinline__ void gemm2_tile(const bf16_t* __restrict__ hbuf, cons
   const int wm = wv / 4, wn = wv % 4;
   __amdgpu_buffer_rsrc_t rA = make_rsrc(hbuf + static_cast<size_t>(row0) * F, static_cast<size_t>(rows) * F * 2);
   __amdgpu_buffer_rsrc_t rB = make_rsrc(w2, static_cast<size_t>(H) * F * 2);
-  int voff[MI + 4];
+  int voff[MI + 2 * NI];
   dma_offsets<MI>(wv, lane, F * 2, [&](int r) { return min(r, rows - 1); }, voff);
-  dma_offsets<4>(wv, lane, F * 2, [&](int j) { return min(n0 + j, H - 1); }, voff + MI);
-  f32x16 acc[MI][2];
-  zero_acc<MI>(acc);
-  gemm_mainloop<MI, 2, 1, (MI >= 3 ? 2 : 3), true>(rA, rB, voff, 0, F, smem, wv, lane, acc);
+  dma_offsets<2 * NI>(wv, lane, F * 2, [&](int j) { return min(n0 + j, H - 1); }, voff + MI);
+  f32x16 acc[MI][NI];
+  zero_acc<MI, NI>(acc);
+  gemm_mainloop<MI, NI, 1, NST, true>(rA, rB, voff, 0, F, smem, wv, lane, acc);
 
   const int valid = min(rows, 64 * MI);  // rows past it are dropped by the descriptor's bounds check
   __amdgpu_buffer_rsrc_t rY = make_rsrc(y + static_cast<size_t>(row0) * H, static_cast<size_t>(valid) * H * 2);
@@ -358,8 +371,8 @@ __device__ __forceinline__ void gemm2_tile(const bf16_t* __restrict__ hbuf, cons
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi) {
 #pragma unroll
-    for (int ni = 0; ni < 2; ++ni) {
-      const int cbase = n0 + 64 * wn + 32 * ni + 8 * (lane >> 5);
+    for (int ni = 0; ni < NI; ++ni) {
+      const int cbase = n0 + 32 * NI * wn + 32 * ni + 8 * (lane >> 5);
       const int off = ((row_in + 32 * mi) * H + cbase) * 2;
 #pragma unroll
       for (int g = 0; g < 2; ++g) {
@@ -400,14 +413,58 @@ __global__ __launch_bounds__(512, 2) void ffn_gemm2_kernel(const bf16_t* __restr
 #endif
 }
 
+// ---- decode schedule: skinny tiles -------------------------------------------------------------
+// When every slot holds a few rows (a decode step: rows per slot of the order of ten), the grouped GEMM does
+// almost no arithmetic per weight byte (the small-n end of eta_g(n), Sec. 3.2) and the call is a stream
+// of every active slot's weights through the chip.  What matters then is that every CU pulls a distinct
+// slice at all times, so the work is cut finer and kept resident: tiles of 64 rows x 64 h columns (gemm1:
+// 64 gate + 64 up weight rows) or 64 rows x 128 output columns (gemm2), three LDS stages of 24 KB, two
+// workgroups per CU (sixteen waves, 72 KB of LDS each), one work item per workgroup in table order.  A
+// slot with more than 64 rows is simply several row tiles: correct for any input, tuned for short slots.
+constexpr int kSkinnyLdsBytes = 3 * (64 + 128) * 128;  // 72 KB
+constexpr int kSkinnyCols1 = 64, kSkinnyCols2 = 128;   // h columns / y columns per work item
+
+template <bool GATHER>
+__global__ __launch_bounds__(512, 4) void ffn_gemm1_skinny_kernel(RowSource src, const int32_t* __restrict__ table,
+                                                                  int H, int F, bf16_t* __restrict__ hbuf) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  extern __shared__ u32x4 smem[];
+  const int n_cols = (F + kSkinnyCols1 - 1) / kSkinnyCols1;
+  const int tile = blockIdx.x / n_cols, col = blockIdx.x % n_cols;
+  if (tile >= table[0]) return;
+  const TileEntry e = reinterpret_cast<const TileEntry*>(table + 8)[tile];
+  gemm1_tile<1, GATHER, 1, 3>(src, static_cast<const bf16_t*>(e.w13), e.row0, e.rows, col * kSkinnyCols1, H, F, hbuf,
+                              smem);
+#endif
+}
+
+__global__ __launch_bounds__(512, 4) void ffn_gemm2_skinny_kernel(const bf16_t* __restrict__ hbuf,
+                                                                  const int32_t* __restrict__ table, int H, int F,
+                                                                  bf16_t* __restrict__ y) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  extern __shared__ u32x4 smem[];
+  const int n_cols = (H + kSkinnyCols2 - 1) / kSkinnyCols2;
+  const int tile = blockIdx.x / n_cols, col = blockIdx.x % n_cols;
+  if (tile >= table[0]) return;
+  const TileEntry e = reinterpret_cast<const TileEntry*>(table + 8)[tile];
+  gemm2_tile<1, 1, 3>(hbuf, static_cast<const bf16_t*>(e.w2), e.row0, e.rows, col * kSkinnyCols2, H, F, y, smem);
+#endif
+}
+
 struct FfnShape {
+  bool skinny;  // the decode schedule
   int max_tiles;
   size_t h_bytes, table_bytes;
 };
 
+// The decode schedule is chosen on the host from the capacity of the row space alone (the row counts live
+// on the device): at most kSkinnyRowsPerSlot rows per slot on average even if every pair were local.
+constexpr int kSkinnyRowsPerSlot = 64;
+
 static FfnShape ffn_shape(int S, int F, int max_rows) {
   FfnShape s;
-  s.max_tiles = max_rows / 256 + S;
+  s.skinny = static_cast<long>(max_rows) <= static_cast<long>(kSkinnyRowsPerSlot) * S;
+  s.max_tiles = s.skinny ? max_rows / 64 + S : max_rows / 256 + S;
   s.h_bytes = align_up(static_cast<size_t>(max_rows > 0 ? max_rows : 1) * F * sizeof(bf16_t), 256);
   s.table_bytes = align_up((1 + static_cast<size_t>(s.max_tiles)) * sizeof(TileEntry), 256);
   return s;
@@ -432,6 +489,15 @@ static int ffn_prepare() {
   if (err == hipSuccess)
     err = hipFuncSetAttribute(reinterpret_cast<const void*>(ffn_gemm2_kernel),
                               hipFuncAttributeMaxDynamicSharedMemorySize, kFfnLdsBytes);
+  if (err == hipSuccess)
+    err = hipFuncSetAttribute(reinterpret_cast<const void*>(ffn_gemm1_skinny_kernel<false>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, kSkinnyLdsBytes);
+  if (err == hipSuccess)
+    err = hipFuncSetAttribute(reinterpret_cast<const void*>(ffn_gemm1_skinny_kernel<true>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, kSkinnyLdsBytes);
+  if (err == hipSuccess)
+    err = hipFuncSetAttribute(reinterpret_cast<const void*>(ffn_gemm2_skinny_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, kSkinnyLdsBytes);
   if (err != hipSuccess) {
     set_error("probe_grouped_ffn: cannot reserve %d bytes of LDS: %s", kFfnLdsBytes, hipGetErrorString(err));
     return PROBE_EHIP;
@@ -488,12 +554,23 @@ static int ffn_impl(const char* name, const void* act_bf16, const int32_t* row_p
   bf16_t* hbuf = static_cast<bf16_t*>(workspace);
   int32_t* table = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + sh.h_bytes);
   hipLaunchKernelGGL(ffn_schedule_kernel, dim3(1), dim3(256), 0, st, slot_offsets, w13_ptrs, w2_ptrs, S, sh.max_tiles,
-                     table);
+                     sh.skinny ? 1 : 0, table);
   RowSource src;
   src.base = static_cast<const bf16_t*>(act_bf16);
   src.row_pair = row_pair;
   src.k = gather ? k : 1;
   src.n_tokens = gather ? T : 0;
+  if (sh.skinny) {
+    const dim3 g1(sh.max_tiles * ((F + kSkinnyCols1 - 1) / kSkinnyCols1));
+    const dim3 g2(sh.max_tiles * ((H + kSkinnyCols2 - 1) / kSkinnyCols2));
+    if (gather)
+      hipLaunchKernelGGL(ffn_gemm1_skinny_kernel<true>, g1, dim3(512), kSkinnyLdsBytes, st, src, table, H, F, hbuf);
+    else
+      hipLaunchKernelGGL(ffn_gemm1_skinny_kernel<false>, g1, dim3(512), kSkinnyLdsBytes, st, src, table, H, F, hbuf);
+    hipLaunchKernelGGL(ffn_gemm2_skinny_kernel, g2, dim3(512), kSkinnyLdsBytes, st, hbuf, table, H, F,
+                       static_cast<bf16_t*>(y_bf16));
+    return check_launch(name);
+  }
   const dim3 grid1(ffn_grid(sh.max_tiles, (F + 127) / 128));
   if (gather)
     hipLaunchKernelGGL(ffn_gemm1_kernel<true>, grid1, dim3(512), kFfnLdsBytes, st, src, table, H, F, hbuf);

@@ -2,14 +2,16 @@
 //
 // The gate is x[T,H] (bf16) times w_gate[E,H] (fp32).  At E = 128..256 this is far above the
 // fp32 vector ridge of the chip, so the product runs on the bf16 MFMA units without giving up
-// fp32 weights: every weight is split once per call into three bf16 planes hi + mid + lo
+// fp32 weights: every weight is split (once, by probe_pack_gate, or inside the call) into three bf16 planes hi + mid + lo
 // (each the round-to-nearest bf16 of what the previous planes left over), which together
 // carry all 24 significand bits.  x is bf16 already, every bf16 x bf16 product is exact in
 // fp32, and the MFMA accumulates in fp32.
 //
-//   1. split    w_gate -> planes[3][E][H] bf16 in the workspace; zero the expert counts
+//   1. split    w_gate -> planes[3][E][H] bf16 in the workspace (skipped by the *_packed entry points,
+//               which are handed planes made once by probe_pack_gate)
 //   2. gemm     split-K tiled GEMM (128 tokens x 128 experts x 64 k per step), three MFMAs per
-//               operand pair (one per plane) into one accumulator  -> partial[KS][T][E] fp32
+//               operand pair (one per plane) into one accumulator  -> partial[KS][T][E] fp32;
+//               its first workgroup clears the expert counts
 //               H % 64 == 0: DMA-to-LDS software pipeline shared with the grouped FFN;
 //               otherwise a register-staged kernel that zero-fills the K tail
 //   3. softmax  sixteen lanes per token: sum the KS partials in fixed order, add the bias,
@@ -53,17 +55,29 @@ __global__ __launch_bounds__(256) void gate_split_kernel(const float* __restrict
   planes[2 * plane_stride + gid] = lo;
 }
 
+// The expert counts that the softmax / top-k kernel adds to are cleared by the first workgroup of
+// the GEMM that precedes it on the stream (n <= 256 <= threads per workgroup).
+__device__ __forceinline__ void zero_counts(int32_t* __restrict__ a, int32_t* __restrict__ b, int n) {
+  if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && static_cast<int>(threadIdx.x) < n) {
+    if (a) a[threadIdx.x] = 0;
+    if (b) b[threadIdx.x] = 0;
+  }
+}
+
 // ---- 2. gemm --------------------------------------------------------------------------
 template <int PL>
 __global__ __launch_bounds__(256, 2) void gate_gemm_kernel(const bf16_t* __restrict__ x,
                                                            const bf16_t* __restrict__ planes,
                                                            int T, int H, int E, int k_chunk,
-                                                           float* __restrict__ partial) {
+                                                           float* __restrict__ partial,
+                                                           int32_t* __restrict__ zero0, int32_t* __restrict__ zero1,
+                                                           int n_zero) {
   __shared__ u32x4 sA[GBM * 8];
   __shared__ u32x4 sB[PL][GBN * 8];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int wm = wv >> 1, wn = wv & 1;
   const int m0 = blockIdx.x * GBM, n0 = blockIdx.y * GBN, ks = blockIdx.z;
+  zero_counts(zero0, zero1, n_zero);
   const int kbeg = ks * k_chunk, kend = min(H, kbeg + k_chunk);
   const long plane_elems = static_cast<long>(E) * H;
 
@@ -162,13 +176,16 @@ template <int MI, int PL>
 __global__ __launch_bounds__(512, 2) void gate_gemm_dma_kernel(const bf16_t* __restrict__ x,
                                                                const bf16_t* __restrict__ planes,
                                                                int T, int H, int E, int k_chunk,
-                                                               float* __restrict__ partial) {
+                                                               float* __restrict__ partial,
+                                                               int32_t* __restrict__ zero0,
+                                                               int32_t* __restrict__ zero1, int n_zero) {
 #if defined(__HIP_DEVICE_COMPILE__)
   extern __shared__ u32x4 smem[];
   const int lane = threadIdx.x & 63;
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wv / 4, wn = wv % 4;
   const int m0 = blockIdx.x * (64 * MI), n0 = blockIdx.y * GBN, ks = blockIdx.z;
+  zero_counts(zero0, zero1, n_zero);
   const int kbeg = ks * k_chunk, klen = min(H, kbeg + k_chunk) - kbeg;
   if (klen <= 0) return;
   const int rows = T - m0;
@@ -828,18 +845,19 @@ static RouteShape route_shape(int T, int H, int E, int max_split = kMaxSplitK) {
 // x [T,H] times a stack of PL bf16 planes [PL][N][H] -> partial [ks][T][N] fp32
 template <int PL>
 static void launch_gate_gemm(const RouteShape& sh, hipStream_t st, const bf16_t* x, const bf16_t* planes, int T,
-                             int H, int N, float* partial) {
+                             int H, int N, float* partial, int32_t* zero0 = nullptr, int32_t* zero1 = nullptr,
+                             int n_zero = 0) {
   if (sh.dma) {
     const int lds = 2 * (sh.bm + 128 * PL) * 128;
     if (sh.bm == 256)
       hipLaunchKernelGGL((gate_gemm_dma_kernel<4, PL>), dim3(sh.mt, sh.nt, sh.ks), dim3(512), lds, st, x, planes, T,
-                         H, N, sh.k_chunk, partial);
+                         H, N, sh.k_chunk, partial, zero0, zero1, n_zero);
     else
       hipLaunchKernelGGL((gate_gemm_dma_kernel<2, PL>), dim3(sh.mt, sh.nt, sh.ks), dim3(512), lds, st, x, planes, T,
-                         H, N, sh.k_chunk, partial);
+                         H, N, sh.k_chunk, partial, zero0, zero1, n_zero);
   } else {
     hipLaunchKernelGGL(gate_gemm_kernel<PL>, dim3(sh.mt, sh.nt, sh.ks), dim3(256), 0, st, x, planes, T, H, N,
-                       sh.k_chunk, partial);
+                       sh.k_chunk, partial, zero0, zero1, n_zero);
   }
 }
 
@@ -849,9 +867,10 @@ struct RouteLayout {
   size_t partial_bytes, upartial_bytes, a_bytes, b_bytes, total;
 };
 
-static RouteLayout route_layout(int T, int H, int E, int D) {
+static RouteLayout route_layout(int T, int H, int E, int D, bool packed = false) {
   RouteLayout L;
   L.gate = route_shape(T, H, E);
+  if (packed) L.gate.planes_bytes = 0;  // the caller holds the planes (probe_pack_gate)
   const size_t plane = static_cast<size_t>(T > 0 ? T : 1) * E * sizeof(float);
   L.upartial_bytes = L.a_bytes = L.b_bytes = 0;
   int extra = 0;
@@ -874,7 +893,9 @@ static int route_impl(const char* name, const void* x_bf16, const float* w_gate,
                       int bias_groups, int tokens_per_group, const void* w1_hat, const float* w2_hat, int D,
                       int T, int H, int E, int k, int renormalize, int32_t* topk_idx, float* topk_w,
                       float* probs, int32_t* expert_counts, void* workspace, size_t workspace_bytes,
-                      void* stream, const probe_gating* gating = nullptr, const float* select_bias = nullptr) {
+                      void* stream, const probe_gating* gating = nullptr, const float* select_bias = nullptr,
+                      const void* packed = nullptr) {
+  // w_gate (fp32, split into planes inside the call) or packed (planes made once by probe_pack_gate)
   PROBE_REQUIRE(T >= 0 && H > 0 && E > 0 && k > 0 && k <= E, PROBE_EINVAL,
                 "%s: bad dims T=%d H=%d E=%d k=%d", name, T, H, E, k);
   PROBE_REQUIRE(bias == nullptr || (bias_groups >= 1 && tokens_per_group >= 1), PROBE_EINVAL,
@@ -896,10 +917,12 @@ static int route_impl(const char* name, const void* x_bf16, const float* w_gate,
                   PROBE_MAX_GROUPS, g.n_group);
     PROBE_REQUIRE(aligned16(select_bias), PROBE_EALIGN, "%s: select_bias must be 16-byte aligned", name);
   }
-  PROBE_REQUIRE(w_gate != nullptr, PROBE_EINVAL, "%s: w_gate is NULL", name);
+  PROBE_REQUIRE(w_gate != nullptr || packed != nullptr, PROBE_EINVAL, "%s: the gate is NULL", name);
   PROBE_REQUIRE(T == 0 || (x_bf16 && topk_idx && topk_w), PROBE_EINVAL, "%s: null pointer", name);
-  PROBE_REQUIRE(aligned16(x_bf16) && aligned16(w_gate), PROBE_EALIGN,
-                "%s: x and w_gate must be 16-byte aligned", name);
+  PROBE_REQUIRE(aligned16(x_bf16) && aligned16(w_gate) && aligned16(packed), PROBE_EALIGN,
+                "%s: x and the gate must be 16-byte aligned", name);
+  PROBE_REQUIRE(aligned16(bias) && aligned16(probs), PROBE_EALIGN,
+                "%s: bias and probs must be 16-byte aligned", name);
   const bool resid = D > 0;
   if (resid) {
     PROBE_REQUIRE(w1_hat && w2_hat, PROBE_EINVAL, "%s: residual weights are NULL", name);
@@ -908,7 +931,7 @@ static int route_impl(const char* name, const void* x_bf16, const float* w_gate,
     PROBE_REQUIRE(aligned16(w1_hat) && aligned16(w2_hat), PROBE_EALIGN,
                   "%s: w1_hat and w2_hat must be 16-byte aligned", name);
   }
-  RouteLayout L = route_layout(T, H, E, resid ? D : 0);
+  RouteLayout L = route_layout(T, H, E, resid ? D : 0, packed != nullptr);
   const RouteShape& sh = L.gate;
   PROBE_REQUIRE(workspace && aligned16(workspace) && workspace_bytes >= L.total, PROBE_EWORKSPACE,
                 "%s: workspace too small or misaligned (%zu < %zu)", name, workspace_bytes, L.total);
@@ -918,16 +941,22 @@ static int route_impl(const char* name, const void* x_bf16, const float* w_gate,
   }
   hipStream_t st = static_cast<hipStream_t>(stream);
   const bf16_t* x = static_cast<const bf16_t*>(x_bf16);
-  bf16_t* planes = static_cast<bf16_t*>(workspace);
+  const bf16_t* planes = static_cast<const bf16_t*>(packed);
   float* partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + sh.planes_bytes);
   float* upartial = reinterpret_cast<float*>(static_cast<char*>(workspace) + sh.planes_bytes + L.partial_bytes);
-  long n = static_cast<long>(E) * H;
-  if (T == 0) n = 0;  // nothing to route: only the counts are cleared
-  long split_threads = n > E ? n : E;
-  hipLaunchKernelGGL(gate_split_kernel, dim3(static_cast<unsigned>((split_threads + 255) / 256)), dim3(256),
-                     0, st, w_gate, n, planes, n, expert_counts, E);
+  const long n = static_cast<long>(E) * H;
+  if (T == 0) {  // nothing to route: only the counts are cleared
+    if (expert_counts)
+      hipLaunchKernelGGL(gate_split_kernel, dim3((E + 255) / 256), dim3(256), 0, st, w_gate, 0l, nullptr, 0l,
+                         expert_counts, E);
+  } else if (packed == nullptr) {
+    bf16_t* ws_planes = static_cast<bf16_t*>(workspace);
+    hipLaunchKernelGGL(gate_split_kernel, dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0, st, w_gate, n,
+                       ws_planes, n, nullptr, E);
+    planes = ws_planes;
+  }
   if (T > 0) {
-    launch_gate_gemm<3>(sh, st, x, planes, T, H, E, partial);
+    launch_gate_gemm<3>(sh, st, x, planes, T, H, E, partial, expert_counts, nullptr, expert_counts ? E : 0);
     int planes_to_sum = sh.ks;
     if (resid) {
       // u = W1_hat h (one bf16 plane); s = silu(u) and W2_hat split into planes; r = W2_hat s as
@@ -985,8 +1014,10 @@ static int route_predict_impl(const void* x_bf16, const float* w_gate, const flo
                               int tokens_per_group, int T, int H, int E, int k, int renormalize,
                               int32_t* topk_idx, float* topk_w, float* probs, int32_t* expert_counts,
                               int32_t* pred_idx, float* pred_w, float* pred_probs, int32_t* pred_counts,
-                              void* workspace, size_t workspace_bytes, void* stream) {
-  const char* name = "probe_route_predict_topk";
+                              void* workspace, size_t workspace_bytes, void* stream,
+                              const void* packed_stack = nullptr) {
+  // (w_gate, w_gate_next) in fp32, or packed_stack: both gates packed into one stack of 2E rows
+  const char* name = packed_stack ? "probe_route_predict_topk_packed" : "probe_route_predict_topk";
   PROBE_REQUIRE(T >= 0 && H > 0 && E > 0 && k > 0 && k <= E, PROBE_EINVAL,
                 "%s: bad dims T=%d H=%d E=%d k=%d", name, T, H, E, k);
   PROBE_REQUIRE((bias == nullptr && bias_next == nullptr) || (bias_groups >= 1 && tokens_per_group >= 1),
@@ -994,12 +1025,15 @@ static int route_predict_impl(const void* x_bf16, const float* w_gate, const flo
   PROBE_REQUIRE(E <= PROBE_MAX_EXPERTS && k <= PROBE_MAX_TOPK && H % 8 == 0, PROBE_EUNSUPPORTED,
                 "%s: needs E <= %d, k <= %d, H %% 8 == 0 (E=%d k=%d H=%d)", name, PROBE_MAX_EXPERTS,
                 PROBE_MAX_TOPK, E, k, H);
-  PROBE_REQUIRE(w_gate != nullptr && w_gate_next != nullptr, PROBE_EINVAL, "%s: a gate is NULL", name);
+  PROBE_REQUIRE(packed_stack != nullptr || (w_gate != nullptr && w_gate_next != nullptr), PROBE_EINVAL,
+                "%s: a gate is NULL", name);
   PROBE_REQUIRE(T == 0 || (x_bf16 && topk_idx && topk_w && pred_idx && pred_w), PROBE_EINVAL,
                 "%s: null pointer", name);
-  PROBE_REQUIRE(aligned16(x_bf16) && aligned16(w_gate) && aligned16(w_gate_next), PROBE_EALIGN,
-                "%s: x and the gates must be 16-byte aligned", name);
-  RouteLayout L = route_layout(T, H, 2 * E, 0);
+  PROBE_REQUIRE(aligned16(x_bf16) && aligned16(w_gate) && aligned16(w_gate_next) && aligned16(packed_stack),
+                PROBE_EALIGN, "%s: x and the gates must be 16-byte aligned", name);
+  PROBE_REQUIRE(aligned16(bias) && aligned16(bias_next) && aligned16(probs) && aligned16(pred_probs), PROBE_EALIGN,
+                "%s: biases and probability outputs must be 16-byte aligned", name);
+  RouteLayout L = route_layout(T, H, 2 * E, 0, packed_stack != nullptr);
   const RouteShape& sh = L.gate;
   PROBE_REQUIRE(workspace && aligned16(workspace) && workspace_bytes >= L.total, PROBE_EWORKSPACE,
                 "%s: workspace too small or misaligned (%zu < %zu)", name, workspace_bytes, L.total);
@@ -1008,18 +1042,28 @@ static int route_predict_impl(const void* x_bf16, const float* w_gate, const flo
     if (rc != PROBE_OK) return rc;
   }
   hipStream_t st = static_cast<hipStream_t>(stream);
-  bf16_t* planes = static_cast<bf16_t*>(workspace);  // [3][2E][H]: rows 0..E-1 this layer's gate, E..2E-1 the next
+  // planes [3][2E][H]: rows 0..E-1 this layer's gate, E..2E-1 the next
+  const bf16_t* planes = static_cast<const bf16_t*>(packed_stack);
   float* partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + sh.planes_bytes);
-  long n = static_cast<long>(E) * H;
-  if (T == 0) n = 0;
-  const long split_threads = n > E ? n : E;
-  const unsigned split_grid = static_cast<unsigned>((split_threads + 255) / 256);
-  hipLaunchKernelGGL(gate_split_kernel, dim3(split_grid), dim3(256), 0, st, w_gate, n, planes, 2 * n,
-                     expert_counts, E);
-  hipLaunchKernelGGL(gate_split_kernel, dim3(split_grid), dim3(256), 0, st, w_gate_next, n, planes + n, 2 * n,
-                     pred_counts, E);
+  const long n = static_cast<long>(E) * H;
+  if (T == 0) {  // nothing to route: only the counts are cleared
+    if (expert_counts)
+      hipLaunchKernelGGL(gate_split_kernel, dim3((E + 255) / 256), dim3(256), 0, st, w_gate, 0l, nullptr, 0l,
+                         expert_counts, E);
+    if (pred_counts)
+      hipLaunchKernelGGL(gate_split_kernel, dim3((E + 255) / 256), dim3(256), 0, st, w_gate, 0l, nullptr, 0l,
+                         pred_counts, E);
+  } else if (packed_stack == nullptr) {
+    bf16_t* ws_planes = static_cast<bf16_t*>(workspace);
+    const unsigned split_grid = static_cast<unsigned>((n + 255) / 256);
+    hipLaunchKernelGGL(gate_split_kernel, dim3(split_grid), dim3(256), 0, st, w_gate, n, ws_planes, 2 * n, nullptr, E);
+    hipLaunchKernelGGL(gate_split_kernel, dim3(split_grid), dim3(256), 0, st, w_gate_next, n, ws_planes + n, 2 * n,
+                       nullptr, E);
+    planes = ws_planes;
+  }
   if (T > 0) {
-    launch_gate_gemm<3>(sh, st, static_cast<const bf16_t*>(x_bf16), planes, T, H, 2 * E, partial);
+    launch_gate_gemm<3>(sh, st, static_cast<const bf16_t*>(x_bf16), planes, T, H, 2 * E, partial, expert_counts,
+                        pred_counts, E);
     int grid = (T + 31) / 32;
     if (grid > 4096) grid = 4096;
     const int G1 = bias ? bias_groups : 1, tpg1 = bias ? tokens_per_group : 1;
@@ -1129,4 +1173,90 @@ extern "C" int probe_route_predict_topk(const void* x_bf16, const float* w_gate,
   return probe::route_predict_impl(x_bf16, w_gate, bias, w_gate_next, bias_next, bias_groups, tokens_per_group, T,
                                    H, E, k, renormalize, topk_idx, topk_w, probs, expert_counts, pred_idx, pred_w,
                                    pred_probs, pred_counts, workspace, workspace_bytes, stream);
+}
+
+// ---- the gate packed once -------------------------------------------------------------------
+// The router's (W_L, b_L) are frozen (Sec. 4.2), so the split of the fp32 gate into three bf16 planes
+// need not be repeated on every call: probe_pack_gate writes the planes once, the *_packed entry points
+// take them in place of the fp32 matrix.
+extern "C" size_t probe_pack_gate_bytes(int H, int E_stack) {
+  if (H <= 0 || E_stack <= 0) return 0;
+  return probe::align_up(static_cast<size_t>(3) * E_stack * H * sizeof(probe::bf16_t), 256);
+}
+
+extern "C" int probe_pack_gate(const float* w_gate, int H, int E, int stack_rows, int row_offset,
+                               void* packed, void* stream) {
+  using namespace probe;
+  PROBE_REQUIRE(H > 0 && E > 0 && stack_rows >= E && row_offset >= 0 && row_offset + E <= stack_rows, PROBE_EINVAL,
+                "probe_pack_gate: bad dims H=%d E=%d stack_rows=%d row_offset=%d", H, E, stack_rows, row_offset);
+  PROBE_REQUIRE(H % 8 == 0, PROBE_EUNSUPPORTED, "probe_pack_gate: needs H %% 8 == 0 (H=%d)", H);
+  PROBE_REQUIRE(w_gate && packed, PROBE_EINVAL, "probe_pack_gate: null pointer");
+  PROBE_REQUIRE(aligned16(w_gate) && aligned16(packed), PROBE_EALIGN,
+                "probe_pack_gate: w_gate and packed must be 16-byte aligned");
+  const long n = static_cast<long>(E) * H;
+  hipLaunchKernelGGL(gate_split_kernel, dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), w_gate, n,
+                     static_cast<bf16_t*>(packed) + static_cast<long>(row_offset) * H,
+                     static_cast<long>(stack_rows) * H, nullptr, E);
+  return check_launch("probe_pack_gate");
+}
+
+extern "C" size_t probe_route_topk_packed_workspace_bytes(int T, int H, int E, int k) {
+  (void)k;
+  if (T < 0 || H <= 0 || E <= 0) return 0;
+  return probe::route_layout(T, H, E, 0, true).total;
+}
+
+extern "C" int probe_route_topk_packed(const void* x_bf16, const void* packed_gate, const float* bias,
+                                       int bias_groups, int tokens_per_group, int T, int H, int E, int k,
+                                       int renormalize, int32_t* topk_idx, float* topk_w, float* probs,
+                                       int32_t* expert_counts, void* workspace, size_t workspace_bytes,
+                                       void* stream) {
+  PROBE_REQUIRE(packed_gate != nullptr, PROBE_EINVAL, "probe_route_topk_packed: packed_gate is NULL");
+  return probe::route_impl("probe_route_topk_packed", x_bf16, nullptr, bias, bias_groups, tokens_per_group, nullptr,
+                           nullptr, 0, T, H, E, k, renormalize, topk_idx, topk_w, probs, expert_counts, workspace,
+                           workspace_bytes, stream, nullptr, nullptr, packed_gate);
+}
+
+extern "C" int probe_predict_topk_packed(const void* h_prev_bf16, const void* packed_gate_next,
+                                         const float* bias_next, int bias_groups, int tokens_per_group, int T,
+                                         int H, int E, int k, int renormalize, int32_t* pred_idx, float* pred_w,
+                                         float* probs, int32_t* pred_counts, void* workspace,
+                                         size_t workspace_bytes, void* stream) {
+  PROBE_REQUIRE(packed_gate_next != nullptr, PROBE_EINVAL, "probe_predict_topk_packed: packed_gate_next is NULL");
+  return probe::route_impl("probe_predict_topk_packed", h_prev_bf16, nullptr, bias_next, bias_groups,
+                           tokens_per_group, nullptr, nullptr, 0, T, H, E, k, renormalize, pred_idx, pred_w, probs,
+                           pred_counts, workspace, workspace_bytes, stream, nullptr, nullptr, packed_gate_next);
+}
+
+extern "C" int probe_route_grouped_packed(const void* x_bf16, const void* packed_gate, const float* bias,
+                                          int bias_groups, int tokens_per_group, const float* select_bias,
+                                          const probe_gating* gating, int T, int H, int E, int k,
+                                          int32_t* topk_idx, float* topk_w, float* scores,
+                                          int32_t* expert_counts, void* workspace, size_t workspace_bytes,
+                                          void* stream) {
+  PROBE_REQUIRE(gating != nullptr, PROBE_EINVAL, "probe_route_grouped_packed: gating is NULL");
+  PROBE_REQUIRE(packed_gate != nullptr, PROBE_EINVAL, "probe_route_grouped_packed: packed_gate is NULL");
+  return probe::route_impl("probe_route_grouped_packed", x_bf16, nullptr, bias, bias_groups, tokens_per_group,
+                           nullptr, nullptr, 0, T, H, E, k, gating->renormalize, topk_idx, topk_w, scores,
+                           expert_counts, workspace, workspace_bytes, stream, gating, select_bias, packed_gate);
+}
+
+extern "C" size_t probe_route_predict_topk_packed_workspace_bytes(int T, int H, int E, int k) {
+  (void)k;
+  if (T < 0 || H <= 0 || E <= 0) return 0;
+  return probe::route_layout(T, H, 2 * E, 0, true).total;
+}
+
+extern "C" int probe_route_predict_topk_packed(const void* x_bf16, const void* packed_stack, const float* bias,
+                                               const float* bias_next, int bias_groups, int tokens_per_group,
+                                               int T, int H, int E, int k, int renormalize, int32_t* topk_idx,
+                                               float* topk_w, float* probs, int32_t* expert_counts,
+                                               int32_t* pred_idx, float* pred_w, float* pred_probs,
+                                               int32_t* pred_counts, void* workspace, size_t workspace_bytes,
+                                               void* stream) {
+  PROBE_REQUIRE(packed_stack != nullptr, PROBE_EINVAL, "probe_route_predict_topk_packed: packed_stack is NULL");
+  return probe::route_predict_impl(x_bf16, nullptr, bias, nullptr, bias_next, bias_groups, tokens_per_group, T, H, E,
+                                   k, renormalize, topk_idx, topk_w, probs, expert_counts, pred_idx, pred_w,
+                                   pred_probs, pred_counts, workspace, workspace_bytes, stream, packed_stack);
 }

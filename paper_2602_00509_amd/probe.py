@@ -79,6 +79,22 @@ def lib():
         L.probe_route_grouped.restype = C.c_int
         L.probe_route_grouped.argtypes = ([C.c_void_p] * 3 + [C.c_int] * 2 + [C.c_void_p, C.POINTER(_Gating)] +
                                           [C.c_int] * 4 + [C.c_void_p] * 5 + [C.c_size_t, C.c_void_p])
+        L.probe_pack_gate_bytes.restype = C.c_size_t
+        L.probe_pack_gate_bytes.argtypes = [C.c_int, C.c_int]
+        L.probe_pack_gate.restype = C.c_int
+        L.probe_pack_gate.argtypes = [C.c_void_p] + [C.c_int] * 4 + [C.c_void_p, C.c_void_p]
+        for name in ("probe_route_topk_packed_workspace_bytes", "probe_route_predict_topk_packed_workspace_bytes"):
+            getattr(L, name).restype = C.c_size_t
+            getattr(L, name).argtypes = [C.c_int] * 4
+        L.probe_route_topk_packed.argtypes = route_args
+        L.probe_predict_topk_packed.argtypes = route_args
+        L.probe_route_topk_packed.restype = L.probe_predict_topk_packed.restype = C.c_int
+        L.probe_route_grouped_packed.restype = C.c_int
+        L.probe_route_grouped_packed.argtypes = ([C.c_void_p] * 3 + [C.c_int] * 2 + [C.c_void_p, C.POINTER(_Gating)] +
+                                                 [C.c_int] * 4 + [C.c_void_p] * 5 + [C.c_size_t, C.c_void_p])
+        L.probe_route_predict_topk_packed.restype = C.c_int
+        L.probe_route_predict_topk_packed.argtypes = ([C.c_void_p] * 4 + [C.c_int] * 7 + [C.c_void_p] * 9 +
+                                                      [C.c_size_t, C.c_void_p])
         L.probe_route_predict_topk_workspace_bytes.restype = C.c_size_t
         L.probe_route_predict_topk_workspace_bytes.argtypes = [C.c_int] * 4
         L.probe_route_predict_topk.restype = C.c_int
@@ -145,12 +161,48 @@ def predict_topk_residual_workspace_bytes(T, H, E, k, D):
     return int(lib().probe_predict_topk_residual_workspace_bytes(T, H, E, k, D))
 
 
+class PackedGate:
+    """probe_pack_gate: the bf16 planes of one gate, or of two gates stacked (for route_predict_topk).
+
+    ``planes`` is bf16 [3, stack_rows, H]; pass the object wherever a w_gate tensor is accepted."""
+
+    def __init__(self, w_gate, w_gate_next=None, *, stream=None):
+        E, H = w_gate.shape
+        _want(w_gate, torch.float32, (E, H), "w_gate")
+        gates = [w_gate]
+        if w_gate_next is not None:
+            _want(w_gate_next, torch.float32, (E, H), "w_gate_next")
+            gates.append(w_gate_next)
+        self.E, self.H, self.stack_rows = E, H, E * len(gates)
+        nbytes = int(lib().probe_pack_gate_bytes(H, self.stack_rows))
+        self.buf = torch.empty(nbytes, dtype=torch.uint8, device=w_gate.device)
+        for i, g in enumerate(gates):
+            _check(lib().probe_pack_gate(_ptr(g), H, E, self.stack_rows, i * E, _ptr(self.buf), _stream(stream)))
+        self.planes = self.buf[:3 * self.stack_rows * H * 2].view(torch.bfloat16).view(3, self.stack_rows, H)
+        self.device = w_gate.device
+
+    def data_ptr(self):
+        return self.buf.data_ptr()
+
+
+def route_topk_packed_workspace_bytes(T, H, E, k):
+    return int(lib().probe_route_topk_packed_workspace_bytes(T, H, E, k))
+
+
 def _route(fn, x, w_gate, bias, tokens_per_group, k, renormalize, want_probs, want_counts, out,
            workspace, stream, residual=None):
     T, H = x.shape
-    E = w_gate.shape[0]
+    packed = isinstance(w_gate, PackedGate)
     _want(x, torch.bfloat16, (T, H), "x")
-    _want(w_gate, torch.float32, (E, H), "w_gate")
+    if packed:
+        if w_gate.stack_rows != w_gate.E or w_gate.H != H or residual is not None:
+            raise ValueError("a single packed gate with H = %d is needed here" % H)
+        E = w_gate.E
+        fn = {"probe_route_topk": lib().probe_route_topk_packed,
+              "probe_predict_topk": lib().probe_predict_topk_packed}[fn.__name__]
+    else:
+        E = w_gate.shape[0]
+        _want(w_gate, torch.float32, (E, H), "w_gate")
     G = 1
     if bias is not None:
         if bias.dim() == 1:
@@ -174,7 +226,8 @@ def _route(fn, x, w_gate, bias, tokens_per_group, k, renormalize, want_probs, wa
     counts = out.get("counts") if want_counts else None
     tail = (T, H, E, k, int(bool(renormalize)), _ptr(out["idx"]), _ptr(out["w"]), _ptr(probs), _ptr(counts))
     if residual is None:
-        workspace = _ws(workspace, route_topk_workspace_bytes(T, H, E, k), dev)
+        need = route_topk_packed_workspace_bytes(T, H, E, k) if packed else route_topk_workspace_bytes(T, H, E, k)
+        workspace = _ws(workspace, need, dev)
         rc = fn(_ptr(x), _ptr(w_gate), _ptr(bias), G, tpg, *tail, _ptr(workspace), workspace.numel(),
                 _stream(stream))
     else:
@@ -209,9 +262,15 @@ def route_grouped(x, w_gate, bias=None, tokens_per_group=None, select_bias=None,
                   want_scores=False, want_counts=True, out=None, workspace=None, stream=None):
     """probe_route_grouped: group-limited gate; returns dict(idx, w, scores?, counts?)."""
     T, H = x.shape
-    E = w_gate.shape[0]
+    packed = isinstance(w_gate, PackedGate)
     _want(x, torch.bfloat16, (T, H), "x")
-    _want(w_gate, torch.float32, (E, H), "w_gate")
+    if packed:
+        if w_gate.stack_rows != w_gate.E or w_gate.H != H:
+            raise ValueError("a single packed gate with H = %d is needed here" % H)
+        E = w_gate.E
+    else:
+        E = w_gate.shape[0]
+        _want(w_gate, torch.float32, (E, H), "w_gate")
     G = 1
     if bias is not None:
         if bias.dim() == 1:
@@ -234,7 +293,8 @@ def route_grouped(x, w_gate, bias=None, tokens_per_group=None, select_bias=None,
     _want(out["idx"], torch.int32, (T, k), "idx")
     _want(out["w"], torch.float32, (T, k), "w")
     workspace = _ws(workspace, int(lib().probe_route_grouped_workspace_bytes(T, H, E, k)), dev)
-    rc = lib().probe_route_grouped(_ptr(x), _ptr(w_gate), _ptr(bias), G, tpg, _ptr(select_bias), C.byref(gating),
+    fn = lib().probe_route_grouped_packed if packed else lib().probe_route_grouped
+    rc = fn(_ptr(x), _ptr(w_gate), _ptr(bias), G, tpg, _ptr(select_bias), C.byref(gating),
                                    T, H, E, k, _ptr(out["idx"]), _ptr(out["w"]),
                                    _ptr(out.get("scores") if want_scores else None),
                                    _ptr(out.get("counts") if want_counts else None), _ptr(workspace),
@@ -269,10 +329,16 @@ def route_predict_topk(x, w_gate, bias, w_gate_next, bias_next, tokens_per_group
 
     Returns (route dict, predict dict), each with idx, w, counts and optionally probs."""
     T, H = x.shape
-    E = w_gate.shape[0]
+    packed = isinstance(w_gate, PackedGate)
     _want(x, torch.bfloat16, (T, H), "x")
-    _want(w_gate, torch.float32, (E, H), "w_gate")
-    _want(w_gate_next, torch.float32, (E, H), "w_gate_next")
+    if packed:
+        if w_gate.stack_rows != 2 * w_gate.E or w_gate.H != H or w_gate_next is not None:
+            raise ValueError("route_predict_topk takes ONE PackedGate(w_gate, w_gate_next) and w_gate_next=None")
+        E = w_gate.E
+    else:
+        E = w_gate.shape[0]
+        _want(w_gate, torch.float32, (E, H), "w_gate")
+        _want(w_gate_next, torch.float32, (E, H), "w_gate_next")
     G = 1
     biases = []
     for b in (bias, bias_next):
@@ -298,12 +364,18 @@ def route_predict_topk(x, w_gate, bias, w_gate_next, bias_next, tokens_per_group
         _want(o["w"], torch.float32, (T, k), "w")
         outs.append(o)
     r, p = outs
-    workspace = _ws(workspace, route_predict_topk_workspace_bytes(T, H, E, k), dev)
-    rc = lib().probe_route_predict_topk(
-        _ptr(x), _ptr(w_gate), _ptr(biases[0]), _ptr(w_gate_next), _ptr(biases[1]), G, tpg, T, H, E, k,
-        int(bool(renormalize)), _ptr(r["idx"]), _ptr(r["w"]), _ptr(r.get("probs") if want_probs else None),
-        _ptr(r["counts"]), _ptr(p["idx"]), _ptr(p["w"]), _ptr(p.get("probs") if want_probs else None),
-        _ptr(p["counts"]), _ptr(workspace), workspace.numel(), _stream(stream))
+    tail = (G, tpg, T, H, E, k, int(bool(renormalize)), _ptr(r["idx"]), _ptr(r["w"]),
+            _ptr(r.get("probs") if want_probs else None), _ptr(r["counts"]), _ptr(p["idx"]), _ptr(p["w"]),
+            _ptr(p.get("probs") if want_probs else None), _ptr(p["counts"]))
+    if packed:
+        workspace = _ws(workspace, int(lib().probe_route_predict_topk_packed_workspace_bytes(T, H, E, k)), dev)
+        rc = lib().probe_route_predict_topk_packed(_ptr(x), _ptr(w_gate), _ptr(biases[0]), _ptr(biases[1]), *tail,
+                                                   _ptr(workspace), workspace.numel(), _stream(stream))
+    else:
+        workspace = _ws(workspace, route_predict_topk_workspace_bytes(T, H, E, k), dev)
+        rc = lib().probe_route_predict_topk(_ptr(x), _ptr(w_gate), _ptr(biases[0]), _ptr(w_gate_next),
+                                            _ptr(biases[1]), *tail, _ptr(workspace), workspace.numel(),
+                                            _stream(stream))
     _check(rc)
     return r, p
 

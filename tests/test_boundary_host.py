@@ -121,6 +121,21 @@ def test_bad_arguments_are_rejected_without_a_launch(L):
     assert L.probe_permute(fake, C.byref(plan), fake, 16, 64, 8, 2, fake, fake, fake, fake, fake, fake, fake, C.c_size_t(0), None) == -4
     bad = _Plan(0x1000, 0x1000, 0x1000, 2000)
     assert L.probe_permute(fake, C.byref(bad), fake, 16, 64, 8, 2, fake, fake, fake, fake, fake, fake, fake, big, None) == -2
+    # packed gate
+    assert L.probe_pack_gate_bytes(7168, 256) >= 3 * 256 * 7168 * 2
+    assert L.probe_pack_gate(None, 64, 8, 8, 0, fake, None) == -1
+    assert L.probe_pack_gate(fake, 64, 8, 8, 1, fake, None) == -1                    # rows past the stack
+    assert L.probe_pack_gate(fake, 60, 8, 8, 0, fake, None) == -2
+    assert L.probe_pack_gate(fake, 64, 8, 8, 0, odd, None) == -3
+    for fn in (L.probe_route_topk_packed, L.probe_predict_topk_packed):
+        assert fn(fake, None, None, 1, 1, 16, 64, 8, 2, 1, fake, fake, None, None, fake, big, None) == -1   # planes NULL
+        assert fn(fake, odd, None, 1, 1, 16, 64, 8, 2, 1, fake, fake, None, None, fake, big, None) == -3
+        assert fn(fake, fake, None, 1, 1, 16, 64, 8, 2, 1, fake, fake, None, None, fake, C.c_size_t(16), None) == -4
+    assert L.probe_route_topk_packed_workspace_bytes(16, 64, 8, 2) < L.probe_route_topk_workspace_bytes(16, 64, 8, 2)
+    # bias and probability outputs are read / written with 16-byte accesses: misaligned ones are refused
+    for fn in (L.probe_route_topk, L.probe_predict_topk):
+        assert fn(fake, fake, C.c_void_p(0x1004), 1, 1, 16, 64, 8, 2, 1, fake, fake, None, None, fake, big, None) == -3
+        assert fn(fake, fake, None, 1, 1, 16, 64, 8, 2, 1, fake, fake, C.c_void_p(0x1004), None, fake, big, None) == -3
     # grouped ffn
     assert L.probe_grouped_ffn(fake, fake, fake, fake, 4, 100, 128, 64, fake, fake, big, None) == -2      # H % 64
     assert L.probe_grouped_ffn(fake, fake, fake, fake, 4, 128, 96, 64, fake, fake, big, None) == -2       # F % 64

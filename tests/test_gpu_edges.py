@@ -261,6 +261,48 @@ def test_ffn_every_way_a_slot_is_cut_into_tiles(oracle, probe, G):
     assert (got[n:] == 7.0).all()          # rows past the last slot are not written
 
 
+def _ffn_against_oracle(oracle, probe, G, cfg, sizes, n_weights, seed, extra_rows=9):
+    """probe_grouped_ffn on slots of the given sizes, every output element against the oracle."""
+    S = len(sizes)
+    so = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    n = int(so[-1])
+    ws = wl.expert_weights_many(cfg, list(range(n_weights)))
+    rng = np.random.default_rng(seed)
+    xp = wl.f32_to_bf16_bits(rng.standard_normal((n + extra_rows, cfg.H)).astype(np.float32))
+    d_w = {e: (G.dev_bf16(ws[e][0]), G.dev_bf16(ws[e][1])) for e in range(n_weights)}
+    tab = probe.WeightTable([d_w[s % n_weights][0] for s in range(S)], [d_w[s % n_weights][1] for s in range(S)])
+    y = torch.full((n + extra_rows, cfg.H), 7.0, dtype=torch.bfloat16, device="cuda")
+    probe.grouped_ffn(G.dev_bf16(xp), torch.from_numpy(so).cuda(), tab, out=y)
+    torch.cuda.synchronize()
+    ref = oracle.grouped_ffn(xp, so, [ws[s % n_weights][0] for s in range(S)], [ws[s % n_weights][1] for s in range(S)])
+    got = G.f64_of(y)
+    err = G.rel_err(got[:n], ref)
+    assert err < G.BF16_RTOL, err
+    assert (got[n:] == 7.0).all()          # rows past the last slot are not written
+    return err
+
+
+def test_ffn_decode_schedule_every_element(oracle, probe, G):
+    """A decode-sized row space (at most 64 rows per slot on average): the call takes the schedule of skinny
+    tiles (64 rows x 64 h columns / 128 output columns).  Slot sizes around the 64-row tile boundary, empty
+    slots, slots of several row tiles; F and H that leave a partial last column block."""
+    for (H, F, cid) in ((192, 320, 96), (128, 64, 97), (256, 448, 98)):
+        cfg = wl.small_config(T=64, H=H, E=4, k=2, F=F, cid=cid)
+        sizes = [0, 1, 40, 63, 64, 65, 0, 130, 17, 33, 5, 0, 90, 2]
+        assert sum(sizes) + 9 <= 64 * len(sizes)
+        print("case decode schedule H=%d F=%d" % (H, F), flush=True)
+        _ffn_against_oracle(oracle, probe, G, cfg, sizes, 4, seed=H + F)
+
+
+def test_ffn_every_tile_height_at_full_depth(oracle, probe, G):
+    """One slot per tile height (320, 256, 192, 128, 64 rows) and a ragged one, at the depth of the benchmark's
+    main configuration (K = 7168 in the first GEMM, 2048 in the second: 112 and 32 steps of the main loop):
+    every output element against the oracle."""
+    cfg = wl.CONFIGS[3]
+    print("case full-depth tile heights", flush=True)
+    _ffn_against_oracle(oracle, probe, G, cfg, [320, 256, 192, 128, 64, 37, 0, 321], 3, seed=77)
+
+
 @pytest.mark.parametrize("cid", [1, 4])
 def test_ffn_with_rows_gathered_on_load_equals_ffn_on_the_permuted_copy(oracle, probe, G, cid):
     """probe_permute without the row copy + probe_grouped_ffn_gather give bit for bit the y of the standard
