@@ -18,7 +18,8 @@
  *                       combine step)
  *
  * Variants of these: probe_pack_gate and the *_packed router / predictor calls (the gate's bf16 planes
- * made once instead of per call), probe_route_predict_topk (router and next layer's predictor in one pass over
+ * made once instead of per call), probe_permute_static (no workspace, for callers that cannot
+ * allocate), probe_route_predict_topk (router and next layer's predictor in one pass over
  * the hidden states), probe_route_grouped (a model's group-limited gate in place of the plain
  * top-k), probe_grouped_ffn_gather (activation rows gathered on load, no permuted copy),
  * probe_combine_shared (adds a shared expert's output), probe_plan_dispatch (the plan as the source
@@ -223,6 +224,29 @@ int probe_permute(const int32_t* topk_idx, const probe_plan* plan, const void* x
                   int H, int E, int k, int32_t* slot_counts, int32_t* slot_offsets,
                   int32_t* row_pair, int32_t* pair_row, void* xp_bf16, int32_t* n_local,
                   void* workspace, size_t workspace_bytes, void* stream);
+
+/* probe_permute for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc) and have no workspace to hand over: the same
+ * arguments without `workspace`.  The block histograms that probe_permute keeps in its workspace live
+ * in a static device array of PROBE_PERMUTE_STATIC_SCRATCH_BYTES inside the library instead; every GPU
+ * the library runs on holds its own copy until the process ends.  The call allocates and frees nothing.
+ * Outputs are those of probe_permute, bit for bit.
+ * Limit: probe_permute_workspace_bytes(T, E, k, S) <= PROBE_PERMUTE_STATIC_SCRATCH_BYTES, i.e. at most
+ * probe_permute_static_max_pairs(E) pairs (262144 at E = 256); larger batches return
+ * PROBE_EUNSUPPORTED and launch nothing.  Batches of at most 1024 pairs do not touch the array.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different
+ * streams, or graphs replayed concurrently) race on it and give unspecified index outputs; calls ordered
+ * on one stream are safe, the array carries nothing from one call to the next.  The first call on a
+ * device looks the array's address up (no allocation); make that first call outside a graph capture.
+ */
+#define PROBE_PERMUTE_STATIC_SCRATCH_BYTES (256 * 1024)
+
+size_t probe_permute_static_max_pairs(int E);
+
+int probe_permute_static(const int32_t* topk_idx, const probe_plan* plan, const void* x_bf16, int T,
+                         int H, int E, int k, int32_t* slot_counts, int32_t* slot_offsets,
+                         int32_t* row_pair, int32_t* pair_row, void* xp_bf16, int32_t* n_local,
+                         void* stream);
 
 /* ------------------------------------------------------------------------ grouped FFN ---
  *

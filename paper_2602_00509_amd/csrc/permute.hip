@@ -18,6 +18,8 @@
 //
 // Steps 1-3 touch only T*k integers; step 4 carries the HBM traffic (T*H*2 bytes read at
 // most, n_local*H*2 written).
+#include <mutex>
+
 #include "common.hpp"
 
 namespace probe {
@@ -484,36 +486,17 @@ extern "C" size_t probe_permute_workspace_bytes(int T, int E, int k, int S) {
   return probe::align_up(static_cast<size_t>(U > 0 ? U : 1) * E * sizeof(int32_t), 256);
 }
 
-extern "C" int probe_permute(const int32_t* topk_idx, const probe_plan* plan, const void* x_bf16,
-                             int T, int H, int E, int k, int32_t* slot_counts,
-                             int32_t* slot_offsets, int32_t* row_pair, int32_t* pair_row,
-                             void* xp_bf16, int32_t* n_local, void* workspace,
-                             size_t workspace_bytes, void* stream) {
-  using namespace probe;
-  PROBE_REQUIRE(T >= 0 && H > 0 && E > 0 && k > 0, PROBE_EINVAL,
-                "probe_permute: bad dims T=%d H=%d E=%d k=%d", T, H, E, k);
-  PROBE_REQUIRE(plan != nullptr, PROBE_EINVAL, "probe_permute: plan is NULL");
-  int S = plan->num_slots;
-  PROBE_REQUIRE(S >= 1, PROBE_EINVAL, "probe_permute: plan->num_slots=%d", S);
-  PROBE_REQUIRE(E <= PROBE_MAX_EXPERTS && k <= PROBE_MAX_TOPK && S <= PROBE_MAX_SLOTS && H % 8 == 0,
-                PROBE_EUNSUPPORTED,
-                "probe_permute: needs E <= %d, k <= %d, S <= %d, H %% 8 == 0 (E=%d k=%d S=%d H=%d)",
-                PROBE_MAX_EXPERTS, PROBE_MAX_TOPK, PROBE_MAX_SLOTS, E, k, S, H);
-  PROBE_REQUIRE(static_cast<long>(T) * k < (1l << 31), PROBE_EUNSUPPORTED, "probe_permute: T*k >= 2^31");
-  PROBE_REQUIRE(plan->rep_off && plan->rep_slot && plan->rep_weight, PROBE_EINVAL,
-                "probe_permute: plan array is NULL");
-  PROBE_REQUIRE(slot_counts && slot_offsets && n_local, PROBE_EINVAL, "probe_permute: null output");
-  PROBE_REQUIRE(T == 0 || (topk_idx && row_pair && pair_row && (xp_bf16 == nullptr || x_bf16)), PROBE_EINVAL,
-                "probe_permute: null pointer");
-  PROBE_REQUIRE(aligned16(x_bf16) && aligned16(xp_bf16), PROBE_EALIGN,
-                "probe_permute: x/xp must be 16-byte aligned");
-  PROBE_REQUIRE(workspace && workspace_bytes >= probe_permute_workspace_bytes(T, E, k, S),
-                PROBE_EWORKSPACE, "probe_permute: workspace too small (%zu < %zu)", workspace_bytes,
-                probe_permute_workspace_bytes(T, E, k, S));
-  hipStream_t st = static_cast<hipStream_t>(stream);
+namespace probe {
+
+// Shared body of probe_permute (block histograms in the caller's workspace) and
+// probe_permute_static (block histograms in the library's own static scratch array).
+static int permute_impl(const char* name, const int32_t* topk_idx, const probe_plan* plan, const void* x_bf16,
+                        int T, int H, int E, int k, int32_t* slot_counts, int32_t* slot_offsets,
+                        int32_t* row_pair, int32_t* pair_row, void* xp_bf16, int32_t* n_local, int32_t* seg,
+                        hipStream_t st) {
+  const int S = plan->num_slots;
   int N = T * k;
   int U = num_blocks(N);
-  int32_t* seg = static_cast<int32_t*>(workspace);
   int seg_blocks = U;
   if (U == 1) {
     hipLaunchKernelGGL(permute_small_kernel, dim3(1), dim3(kPermWaves * kWave), 0, st, topk_idx, N, E,
@@ -544,5 +527,107 @@ extern "C" int probe_permute(const int32_t* topk_idx, const probe_plan* plan, co
     }
 #undef PROBE_SCATTER_CASE
   }
-  return check_launch("probe_permute");
+  return check_launch(name);
+}
+
+// Argument checks common to both entry points (everything but the scratch memory).
+static int permute_check(const char* name, const int32_t* topk_idx, const probe_plan* plan, const void* x_bf16,
+                         int T, int H, int E, int k, int32_t* slot_counts, int32_t* slot_offsets,
+                         int32_t* row_pair, int32_t* pair_row, void* xp_bf16, int32_t* n_local) {
+  PROBE_REQUIRE(T >= 0 && H > 0 && E > 0 && k > 0, PROBE_EINVAL, "%s: bad dims T=%d H=%d E=%d k=%d", name, T, H,
+                E, k);
+  PROBE_REQUIRE(plan != nullptr, PROBE_EINVAL, "%s: plan is NULL", name);
+  int S = plan->num_slots;
+  PROBE_REQUIRE(S >= 1, PROBE_EINVAL, "%s: plan->num_slots=%d", name, S);
+  PROBE_REQUIRE(E <= PROBE_MAX_EXPERTS && k <= PROBE_MAX_TOPK && S <= PROBE_MAX_SLOTS && H % 8 == 0,
+                PROBE_EUNSUPPORTED, "%s: needs E <= %d, k <= %d, S <= %d, H %% 8 == 0 (E=%d k=%d S=%d H=%d)", name,
+                PROBE_MAX_EXPERTS, PROBE_MAX_TOPK, PROBE_MAX_SLOTS, E, k, S, H);
+  PROBE_REQUIRE(static_cast<long>(T) * k < (1l << 31), PROBE_EUNSUPPORTED, "%s: T*k >= 2^31", name);
+  PROBE_REQUIRE(plan->rep_off && plan->rep_slot && plan->rep_weight, PROBE_EINVAL, "%s: plan array is NULL", name);
+  PROBE_REQUIRE(slot_counts && slot_offsets && n_local, PROBE_EINVAL, "%s: null output", name);
+  PROBE_REQUIRE(T == 0 || (topk_idx && row_pair && pair_row && (xp_bf16 == nullptr || x_bf16)), PROBE_EINVAL,
+                "%s: null pointer", name);
+  PROBE_REQUIRE(aligned16(x_bf16) && aligned16(xp_bf16), PROBE_EALIGN, "%s: x/xp must be 16-byte aligned", name);
+  return PROBE_OK;
+}
+
+}  // namespace probe
+
+extern "C" int probe_permute(const int32_t* topk_idx, const probe_plan* plan, const void* x_bf16,
+                             int T, int H, int E, int k, int32_t* slot_counts,
+                             int32_t* slot_offsets, int32_t* row_pair, int32_t* pair_row,
+                             void* xp_bf16, int32_t* n_local, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+  using namespace probe;
+  int rc = permute_check("probe_permute", topk_idx, plan, x_bf16, T, H, E, k, slot_counts, slot_offsets, row_pair,
+                         pair_row, xp_bf16, n_local);
+  if (rc != PROBE_OK) return rc;
+  PROBE_REQUIRE(workspace && workspace_bytes >= probe_permute_workspace_bytes(T, E, k, plan->num_slots),
+                PROBE_EWORKSPACE, "probe_permute: workspace too small (%zu < %zu)", workspace_bytes,
+                probe_permute_workspace_bytes(T, E, k, plan->num_slots));
+  return permute_impl("probe_permute", topk_idx, plan, x_bf16, T, H, E, k, slot_counts, slot_offsets, row_pair,
+                      pair_row, xp_bf16, n_local, static_cast<int32_t*>(workspace),
+                      static_cast<hipStream_t>(stream));
+}
+
+// ---- probe_permute_static: the same call for callers that cannot allocate ------------------
+// The block histograms live in a file-scope device array instead of a caller-supplied workspace.
+// Each GPU the library runs on holds its own copy of the array at its own address until the process
+// ends; the address is looked up once per device (hipGetSymbolAddress, no allocation) and passed to
+// the kernels like any workspace pointer.  The histogram kernel writes every entry the later kernels
+// read, so nothing has to be cleared between calls.
+namespace probe {
+
+constexpr size_t kStaticScratchBytes = PROBE_PERMUTE_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) int32_t scratch[kStaticScratchBytes / sizeof(int32_t)];
+
+static int static_scratch(int32_t** out) {
+  static std::mutex mu;
+  static int32_t* ptr_of[64] = {nullptr};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+    set_error("probe_permute_static: no current device");
+    return PROBE_EHIP;
+  }
+  std::lock_guard<std::mutex> lock(mu);
+  if (ptr_of[dev] == nullptr) {
+    void* p = nullptr;
+    hipError_t err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (err != hipSuccess || p == nullptr) {
+      set_error("probe_permute_static: cannot locate the scratch array on device %d: %s", dev,
+                hipGetErrorString(err));
+      return PROBE_EHIP;
+    }
+    ptr_of[dev] = static_cast<int32_t*>(p);
+  }
+  *out = ptr_of[dev];
+  return PROBE_OK;
+}
+
+}  // namespace probe
+
+extern "C" size_t probe_permute_static_max_pairs(int E) {
+  if (E <= 0 || E > PROBE_MAX_EXPERTS) return 0;
+  const size_t blocks = probe::kStaticScratchBytes / (static_cast<size_t>(E) * sizeof(int32_t));
+  return blocks * probe::kSegPairs * probe::kPermWaves;
+}
+
+extern "C" int probe_permute_static(const int32_t* topk_idx, const probe_plan* plan, const void* x_bf16, int T,
+                                    int H, int E, int k, int32_t* slot_counts, int32_t* slot_offsets,
+                                    int32_t* row_pair, int32_t* pair_row, void* xp_bf16, int32_t* n_local,
+                                    void* stream) {
+  using namespace probe;
+  int rc = permute_check("probe_permute_static", topk_idx, plan, x_bf16, T, H, E, k, slot_counts, slot_offsets,
+                         row_pair, pair_row, xp_bf16, n_local);
+  if (rc != PROBE_OK) return rc;
+  const size_t need = probe_permute_workspace_bytes(T, E, k, plan->num_slots);
+  PROBE_REQUIRE(need <= kStaticScratchBytes, PROBE_EUNSUPPORTED,
+                "probe_permute_static: T*k = %ld pairs with E = %d need %zu bytes of block histograms, the static "
+                "scratch holds %zu (at most %zu pairs at this E); use probe_permute with a workspace",
+                static_cast<long>(T) * k, E, need, kStaticScratchBytes, probe_permute_static_max_pairs(E));
+  int32_t* seg = nullptr;
+  rc = static_scratch(&seg);
+  if (rc != PROBE_OK) return rc;
+  return permute_impl("probe_permute_static", topk_idx, plan, x_bf16, T, H, E, k, slot_counts, slot_offsets,
+                      row_pair, pair_row, xp_bf16, n_local, seg, static_cast<hipStream_t>(stream));
 }

@@ -66,6 +66,11 @@ def lib():
         L.probe_predict_topk_residual_workspace_bytes.argtypes = [C.c_int] * 5
         L.probe_permute.argtypes = ([C.c_void_p, C.POINTER(_Plan), C.c_void_p] + [C.c_int] * 4 +
                                     [C.c_void_p] * 7 + [C.c_size_t, C.c_void_p])
+        L.probe_permute_static.restype = C.c_int
+        L.probe_permute_static.argtypes = ([C.c_void_p, C.POINTER(_Plan), C.c_void_p] + [C.c_int] * 4 +
+                                           [C.c_void_p] * 7)
+        L.probe_permute_static_max_pairs.restype = C.c_size_t
+        L.probe_permute_static_max_pairs.argtypes = [C.c_int]
         L.probe_grouped_ffn.argtypes = ([C.c_void_p] * 4 + [C.c_int] * 4 + [C.c_void_p] * 2 +
                                         [C.c_size_t, C.c_void_p])
         L.probe_grouped_ffn_gather.argtypes = ([C.c_void_p] * 2 + [C.c_int] * 2 + [C.c_void_p] * 3 + [C.c_int] * 4 +
@@ -454,7 +459,18 @@ def permute_workspace_bytes(T, E, k, S):
     return int(lib().probe_permute_workspace_bytes(T, E, k, S))
 
 
-def permute(topk_idx, plan: Plan, x, *, out=None, workspace=None, stream=None, copy_rows=True):
+def permute_static_max_pairs(E):
+    return int(lib().probe_permute_static_max_pairs(E))
+
+
+def permute_static(topk_idx, plan: Plan, x, *, out, stream=None, copy_rows=True):
+    """probe_permute_static: probe_permute without a workspace (the library's static scratch array).
+
+    Every output tensor must be passed in ``out`` (this wrapper allocates nothing either)."""
+    return permute(topk_idx, plan, x, out=out, stream=stream, copy_rows=copy_rows, _static=True)
+
+
+def permute(topk_idx, plan: Plan, x, *, out=None, workspace=None, stream=None, copy_rows=True, _static=False):
     """probe_permute: returns dict(slot_counts, slot_offsets, row_pair, pair_row, xp, n_local).
 
     copy_rows=False passes xp = NULL: index outputs only (for grouped_ffn_gather); no "xp" in the result."""
@@ -474,8 +490,17 @@ def permute(topk_idx, plan: Plan, x, *, out=None, workspace=None, stream=None, c
         out.pop("xp", None)
     for name, (shape, dt) in spec.items():
         if name not in out:
+            if _static:
+                raise ValueError("permute_static: output %r must be pre-allocated" % name)
             out[name] = torch.empty(shape, dtype=dt, device=dev)
         _want(out[name], dt, shape, name)
+    if _static:
+        rc = lib().probe_permute_static(_ptr(topk_idx), C.byref(plan.c), _ptr(x), T, H, E, k,
+                                        _ptr(out["slot_counts"]), _ptr(out["slot_offsets"]),
+                                        _ptr(out["row_pair"]), _ptr(out["pair_row"]), _ptr(out.get("xp")),
+                                        _ptr(out["n_local"]), _stream(stream))
+        _check(rc)
+        return out
     workspace = _ws(workspace, permute_workspace_bytes(T, E, k, S), dev)
     rc = lib().probe_permute(_ptr(topk_idx), C.byref(plan.c), _ptr(x), T, H, E, k,
                              _ptr(out["slot_counts"]), _ptr(out["slot_offsets"]),

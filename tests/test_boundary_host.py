@@ -121,6 +121,11 @@ def test_bad_arguments_are_rejected_without_a_launch(L):
     assert L.probe_permute(fake, C.byref(plan), fake, 16, 64, 8, 2, fake, fake, fake, fake, fake, fake, fake, C.c_size_t(0), None) == -4
     bad = _Plan(0x1000, 0x1000, 0x1000, 2000)
     assert L.probe_permute(fake, C.byref(bad), fake, 16, 64, 8, 2, fake, fake, fake, fake, fake, fake, fake, big, None) == -2
+    # permute without a workspace: larger batches than the static scratch array holds are refused
+    assert L.probe_permute_static(fake, C.byref(plan), fake, 40000, 64, 256, 8, fake, fake, fake, fake, fake, fake, None) == -2
+    assert "static" in err() and L.probe_permute_static_max_pairs(256) == 262144
+    assert L.probe_permute_static(fake, None, fake, 16, 64, 8, 2, fake, fake, fake, fake, fake, fake, None) == -1
+    assert L.probe_permute_static(fake, C.byref(plan), odd, 16, 64, 8, 2, fake, fake, fake, fake, fake, fake, None) == -3
     # packed gate
     assert L.probe_pack_gate_bytes(7168, 256) >= 3 * 256 * 7168 * 2
     assert L.probe_pack_gate(None, 64, 8, 8, 0, fake, None) == -1
