@@ -300,7 +300,7 @@ def main():
 
     # what this machine sustains, next to the nominal peaks: MFMA-only loop (no memory instruction) with zero
     # and with random bf16 operands, and a plain streaming copy
-    result["roofline"]["peak_measured"] = measure_peaks(torch, probe, dev)
+    result["roofline"]["peak_measured"] = measure_peaks(torch, dev)
     result["roofline"]["frac_of_measured_mfma_random"] = (
         ffn_tflops / result["roofline"]["peak_measured"]["mfma_only_random_operands_tflops"])
 
@@ -380,7 +380,13 @@ def main():
     print(json.dumps(result), flush=True)
 
 
-def measure_peaks(torch, probe, dev):
+def measure_peaks(torch, dev):
+    import ctypes as C
+    peaks = C.CDLL(os.path.join(ROOT, "paper_2602_00509_amd", "libprobe_peaks.so"))   # bench-only aid, not libprobe
+    peaks.peaks_mfma_flops_per_launch.restype = C.c_double
+    peaks.peaks_mfma_flops_per_launch.argtypes = [C.c_int, C.c_int]
+    peaks.peaks_mfma.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
+
     def timed(fn, reps):
         fn()
         torch.cuda.synchronize()
@@ -395,11 +401,12 @@ def measure_peaks(torch, probe, dev):
     out = torch.empty((wgs * 512,), dtype=torch.float32, device=dev)
     res = {}
     for name, rnd in (("mfma_only_zero_operands_tflops", False), ("mfma_only_random_operands_tflops", True)):
-        flops = [0.0]
         def run():
-            flops[0] = probe.peak_mfma(wgs, iters, rnd, out=out)
+            rc = peaks.peaks_mfma(C.c_void_p(out.data_ptr()), wgs, iters, 1 if rnd else 0,
+                                  C.c_void_p(torch.cuda.current_stream().cuda_stream))
+            assert rc == 0, rc
         t = timed(run, 3)
-        res[name] = flops[0] / t / 1e12
+        res[name] = float(peaks.peaks_mfma_flops_per_launch(wgs, iters)) / t / 1e12
     src = torch.empty((1 << 28,), dtype=torch.float32, device=dev)          # 1 GiB read + 1 GiB write
     dst = torch.empty_like(src)
     src.fill_(1.0)
@@ -419,27 +426,47 @@ def measure_peaks(torch, probe, dev):
 
 
 def cpu_baseline(cfg, x, wg, bias, tpg, plan, host_w, slot_expert, sample_tokens):
-    """The CPU oracle, as it stands, on the first tokens of batch 0 (whole layer per token)."""
+    """The CPU oracle, as it stands, on batch 0, stage by stage (route, permute, FFN, combine).
+
+    The whole batch when the FFN of its local rows fits the time budget (it does for the default workload);
+    otherwise the FFN is timed on the leading rows of the row space until the budget is spent and its time is
+    scaled to all rows, which the `sample` string then says."""
     import oracle
     oracle.build()
-    chunk = 64
-    budget_s = 12.0 if not sample_tokens else 1e9
-    limit = min(sample_tokens or cfg.T, cfg.T)
+    budget_s = 40.0
+    T = min(sample_tokens or cfg.T, cfg.T)
+    xs = np.ascontiguousarray(x[:T])
     w13 = [host_w[int(e)][0] for e in slot_expert]
     w2 = [host_w[int(e)][1] for e in slot_expert]
-    done, rows = 0, 0
-    t0 = time.perf_counter()
-    while done < limit and time.perf_counter() - t0 < budget_s:
-        t1 = min(limit, done + chunk)
-        g = np.minimum(np.arange(done, t1) // tpg, bias.shape[0] - 1)
-        res = oracle.moe_layer(x[done:t1], wg, np.ascontiguousarray(bias[g]), 1, cfg.k, True, plan, w13, w2)
-        rows += res["permute"]["n_local"]
-        done = t1
-        chunk = min(chunk * 2, 1024)
-    dt = time.perf_counter() - t0
-    return {"value": done / dt, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": "first %d tokens of batch 0 through the whole oracle layer in chunks "
-                      "(route, permute, FFN of the %d local rows, combine), %.1f s" % (done, rows, dt)}
+    clock = time.perf_counter
+    t0 = clock()
+    r = oracle.route_topk(xs, wg, bias, tpg, cfg.k, True)
+    t1 = clock()
+    p = oracle.permute(r["idx"], plan["rep_off"], plan["rep_slot"], plan["rep_weight"], plan["num_slots"], xs)
+    t2 = clock()
+    nl = p["n_local"]
+    H = xs.shape[1]
+    y = np.zeros((max(nl, 1), H), np.float64)
+    done, chunk, t_ffn = 0, 256, 0.0
+    while done < nl and t_ffn < budget_s:
+        hi = min(nl, done + chunk)
+        ta = clock()
+        y[done:hi] = oracle.grouped_ffn(p["xp"], p["slot_offsets"], w13, w2, rows=np.arange(done, hi, dtype=np.int32))
+        t_ffn += clock() - ta
+        done = hi
+        chunk = min(chunk * 2, 4096)
+    t3 = clock()
+    oracle.combine(y, p["pair_row"], r["w"])
+    t4 = clock()
+    ffn_full = t_ffn * (nl / done) if done else 0.0
+    stage_s = {"route": t1 - t0, "permute": t2 - t1, "ffn": ffn_full, "combine": t4 - t3}
+    total = sum(stage_s.values())
+    what = ("all %d tokens of batch 0, stage by stage: route, permute, FFN of the %d local rows, combine" % (T, nl)
+            if done == nl else
+            "all %d tokens of batch 0 for route, permute and combine; FFN timed on the first %d of %d local rows "
+            "(%.1f s) and scaled to all of them" % (T, done, nl, t_ffn))
+    return {"value": T / total, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": what + "; %.1f s of CPU work" % (t4 - t0), "stage_s": stage_s}
 
 
 if __name__ == "__main__":

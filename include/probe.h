@@ -474,19 +474,6 @@ int probe_predictor_metrics(const int32_t* pred_idx, int pred_stride, int kp, co
                             const float* true_probs, int E, int64_t* hits, double* cross_entropy_sum,
                             void* stream);
 
-/* -------------------------------------------------------------------- measurement aid ---
- *
- * Not a step of the layer.  An MFMA-only loop (v_mfma_f32_32x32x16_bf16, operands in registers, no
- * memory instruction inside) that bench.py --peaks times to report the matrix-core rate the box
- * sustains next to the nominal peak: `workgroups` workgroups of 8 waves run `iters` iterations of 8
- * MFMAs per wave, with all-zero operands or, if random_operands is non-zero, random bf16 operands.
- *   out  device, fp32 [workgroups * 512] (out, one checksum per thread; keeps the loop alive)
- * probe_peak_mfma_flops_per_launch returns the flops of one such launch (host arithmetic only).
- */
-double probe_peak_mfma_flops_per_launch(int workgroups, int iters);
-
-int probe_peak_mfma(float* out, int workgroups, int iters, int random_operands, void* stream);
-
 #ifdef __cplusplus
 }
 #endif

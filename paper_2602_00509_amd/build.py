@@ -1,4 +1,5 @@
-"""Build libprobe.so (hand-written HIP for gfx950) in-tree with hipcc."""
+"""Build libprobe.so (hand-written HIP for gfx950) in-tree with hipcc, and libprobe_peaks.so, the
+measurement aid that only bench.py loads."""
 from __future__ import annotations
 
 import glob
@@ -10,6 +11,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libprobe.so")
+CSRC_BENCH = os.path.join(HERE, "csrc_bench")
+LIB_PEAKS = os.path.join(HERE, "libprobe_peaks.so")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -23,11 +26,10 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def build(verbose: bool = False) -> str:
-    """Compile every kernel source into libprobe.so; always recompiles."""
+def _compile(srcs, lib, verbose):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    tmp = LIB + ".tmp%d" % os.getpid()
-    cmd = [hipcc] + HIPCC_FLAGS + ["-I" + os.path.join(ROOT, "include"), "-I" + CSRC, "-o", tmp] + sources()
+    tmp = lib + ".tmp%d" % os.getpid()
+    cmd = [hipcc] + HIPCC_FLAGS + ["-I" + os.path.join(ROOT, "include"), "-I" + CSRC, "-o", tmp] + srcs
     if verbose:
         print(" ".join(cmd), flush=True)
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -36,8 +38,14 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, lib)
+    return lib
+
+
+def build(verbose: bool = False) -> str:
+    """Compile every kernel source into libprobe.so and the bench aid into libprobe_peaks.so; always recompiles."""
+    _compile(sorted(glob.glob(os.path.join(CSRC_BENCH, "*.hip"))), LIB_PEAKS, verbose)
+    return _compile(sources(), LIB, verbose)
 
 
 if __name__ == "__main__":

@@ -115,11 +115,8 @@ def lib():
         L.probe_predictor_metrics.restype = C.c_int
         L.probe_predictor_metrics.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int,
                                               C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
-        L.probe_peak_mfma_flops_per_launch.restype = C.c_double
-        L.probe_peak_mfma_flops_per_launch.argtypes = [C.c_int, C.c_int]
-        L.probe_peak_mfma.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
         for name in ("probe_route_topk", "probe_predict_topk", "probe_permute", "probe_grouped_ffn",
-                     "probe_combine", "probe_peak_mfma"):
+                     "probe_combine"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -635,15 +632,6 @@ def predictor_metrics(pred_idx, true_idx, kp=None, kt=None, pred_probs=None, tru
                                          T, _ptr(pred_probs), _ptr(true_probs), E, _ptr(hits), _ptr(ce),
                                          _stream(stream)))
     return hits, ce
-
-
-def peak_mfma(workgroups=256, iters=20000, random_operands=True, *, out=None, stream=None):
-    """probe_peak_mfma: launches the MFMA-only loop; returns the flops of the launch (time it with events)."""
-    if out is None:
-        out = torch.empty((workgroups * 512,), dtype=torch.float32, device="cuda")
-    _want(out, torch.float32, (workgroups * 512,), "out")
-    _check(lib().probe_peak_mfma(_ptr(out), workgroups, iters, 1 if random_operands else 0, _stream(stream)))
-    return float(lib().probe_peak_mfma_flops_per_launch(workgroups, iters))
 
 
 def version() -> str:
