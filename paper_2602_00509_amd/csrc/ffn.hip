@@ -62,6 +62,9 @@ struct alignas(16) TileEntry {
   const void* w2;
 };
 static_assert(sizeof(TileEntry) == 32, "one 32-byte record per tile");
+// Table header, 128 bytes: word 0 = number of tiles; words 8..15 and 16..23 = the work-queue tickets of
+// gemm1 and gemm2 (one counter per XCD), cleared by the schedule kernel of the same call.
+constexpr int kTableHeaderInts = 32, kQueue1 = 8, kQueue2 = 16;
 
 constexpr bool kInterleave = true;
 
@@ -162,7 +165,8 @@ __global__ __launch_bounds__(256) void ffn_schedule_kernel(const int32_t* __rest
   __syncthreads();
   const int total = min(start[S], max_tiles);
   if (tid == 0) table[0] = total;
-  TileEntry* entries = reinterpret_cast<TileEntry*>(table + 8);
+  if (tid >= kQueue1 && tid < kTableHeaderInts) table[tid] = 0;
+  TileEntry* entries = reinterpret_cast<TileEntry*>(table + kTableHeaderInts);
   // positions [0, big) hold the slots of more than 192 rows: tiles [0, nb) are theirs, the ns single
   // short tiles follow
   int big = 0;
@@ -227,17 +231,59 @@ __device__ __forceinline__ void zero_acc(f32x16 (&acc)[MI][NI]) {
 // operand slices through that L2 instead of 18 for a 16 x 2 strip.
 constexpr int kXcds = 8, kBlkM = 8, kBlkN = 4, kBlk = kBlkM * kBlkN;
 
-__device__ __forceinline__ bool ffn_work_item(int n_tiles, int n_cols, int& tile, int& col) {
-  const int L = blockIdx.x;
-  const int xcd = L % kXcds, j = L / kXcds;
-  const int q = ((j / kBlk) * kXcds + xcd) * kBlk + (j % kBlk);  // item number: blocks of 32 per XCD
+__device__ __forceinline__ bool ffn_item_of(int q, int n_tiles, int n_cols, int& tile, int& col) {
+  // item number q: blocks of 32 items; block blk = (tile group, column group), column groups fastest
   const int col_groups = (n_cols + kBlkN - 1) / kBlkN;
   const int blk = q / kBlk, w = q % kBlk;
-  const int tg = blk / col_groups, cg = blk % col_groups;  // column groups vary fastest
+  const int tg = blk / col_groups, cg = blk % col_groups;
   tile = tg * kBlkM + w / kBlkN;
   col = cg * kBlkN + w % kBlkN;
   return tile < n_tiles && col < n_cols;
 }
+
+__device__ __forceinline__ bool ffn_work_item(int n_tiles, int n_cols, int& tile, int& col) {
+  const int L = blockIdx.x;
+  const int xcd = L % kXcds, j = L / kXcds;
+  const int q = ((j / kBlk) * kXcds + xcd) * kBlk + (j % kBlk);  // item number: blocks of 32 per XCD
+  return ffn_item_of(q, n_tiles, n_cols, tile, col);
+}
+
+// Work queue of the persistent launch (one workgroup per CU).  Blocks of 32 items are dealt to the XCDs
+// round-robin as above (block b belongs to XCD b % 8), but which workgroup runs which item is decided at
+// run time: a workgroup draws tickets from the counter of the XCD it runs on (ticket t = item t % 32 of
+// that XCD's (t / 32)-th block), so the 32 workgroups of an XCD still walk one block side by side; when
+// its own XCD's blocks are used up it draws from the next XCD's counter, and so on round the ring, until
+// all eight are exhausted.  Counters only grow and nobody waits for anybody, so every workgroup ends after
+// at most 8 unsuccessful draws.  Returns false when no work is left.
+struct WorkQueue {
+  int32_t* counters;  // [8], cleared by the schedule kernel
+  int victim, misses;
+  __device__ __forceinline__ void init(int32_t* c) {
+    counters = c;
+    victim = __builtin_amdgcn_s_getreg((20 << 0) | (0 << 6) | (3 << 11)) & (kXcds - 1);  // XCC_ID
+    misses = 0;
+  }
+  // all threads of the workgroup call this together; *slot is one int of static LDS
+  __device__ __forceinline__ bool next(int n_tiles, int n_cols, int* slot, int& tile, int& col) {
+    const int col_groups = (n_cols + kBlkN - 1) / kBlkN, tile_groups = (n_tiles + kBlkM - 1) / kBlkM;
+    const int n_blocks = tile_groups * col_groups;
+    while (misses < kXcds) {
+      __syncthreads();  // the previous item is finished by every wave (LDS stages, *slot)
+      if (threadIdx.x == 0) *slot = atomicAdd(&counters[victim], 1);
+      __syncthreads();
+      const int t = *slot;
+      const int b = (t / kBlk) * kXcds + victim;
+      if (b >= n_blocks) {  // this XCD's blocks are used up: go on to the next one's
+        victim = (victim + 1) & (kXcds - 1);
+        ++misses;
+        continue;
+      }
+      misses = 0;
+      if (ffn_item_of(b * kBlk + t % kBlk, n_tiles, n_cols, tile, col)) return true;
+    }
+    return false;
+  }
+};
 
 static int ffn_grid(int max_tiles, int n_cols) {
   const int tile_groups = (max_tiles + kBlkM - 1) / kBlkM, col_groups = (n_cols + kBlkN - 1) / kBlkN;
@@ -325,26 +371,35 @@ __device__ __forceinline__ void gemm1_tile(const RowSource& src, const bf16_t* _
 
 // one-dimensional launch over (row tile, column block) work items; a column block is 128 gate +
 // 128 up weight rows
+// queue != 0: persistent launch, items drawn from the work queue; 0: one workgroup per item
 template <bool GATHER>
-__global__ __launch_bounds__(512, 2) void ffn_gemm1_kernel(RowSource src, const int32_t* __restrict__ table, int H,
-                                                           int F, bf16_t* __restrict__ hbuf) {
+__global__ __launch_bounds__(512, 2) void ffn_gemm1_kernel(RowSource src, const int32_t* __restrict__ table,
+                                                           int32_t* table_rw, int queue, int H, int F,
+                                                           bf16_t* __restrict__ hbuf) {
 #if defined(__HIP_DEVICE_COMPILE__)
   extern __shared__ u32x4 smem[];
+  __shared__ int ticket;
+  const int n_tiles = table[0], n_cols = (F + 127) / 128;
+  WorkQueue wq;
+  if (queue) wq.init(table_rw + kQueue1);
   int tile, col;
-  if (!ffn_work_item(table[0], (F + 127) / 128, tile, col)) return;
-  const TileEntry e = reinterpret_cast<const TileEntry*>(table + 8)[tile];
-  const int n0 = col * 128;
-  const bf16_t* w13 = static_cast<const bf16_t*>(e.w13);
-  if (e.height > 256)
-    gemm1_tile<5, GATHER>(src, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
-  else if (e.height > 192)
-    gemm1_tile<4, GATHER>(src, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
-  else if (e.height > 128)
-    gemm1_tile<3, GATHER>(src, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
-  else if (e.height > 64)
-    gemm1_tile<2, GATHER>(src, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
-  else
-    gemm1_tile<1, GATHER>(src, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
+  if (!queue && !ffn_work_item(n_tiles, n_cols, tile, col)) return;
+  while (!queue || wq.next(n_tiles, n_cols, &ticket, tile, col)) {
+    const TileEntry e = reinterpret_cast<const TileEntry*>(table + kTableHeaderInts)[tile];
+    const int n0 = col * 128;
+    const bf16_t* w13 = static_cast<const bf16_t*>(e.w13);
+    if (e.height > 256)
+      gemm1_tile<5, GATHER>(src, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
+    else if (e.height > 192)
+      gemm1_tile<4, GATHER>(src, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
+    else if (e.height > 128)
+      gemm1_tile<3, GATHER>(src, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
+    else if (e.height > 64)
+      gemm1_tile<2, GATHER>(src, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
+    else
+      gemm1_tile<1, GATHER>(src, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
+    if (!queue) break;
+  }
 #endif
 }
 
@@ -391,25 +446,32 @@ __device__ __forceinline__ void gemm2_tile(const bf16_t* __restrict__ hbuf, cons
 
 // one-dimensional launch over (row tile, column block of 256 output columns) work items
 __global__ __launch_bounds__(512, 2) void ffn_gemm2_kernel(const bf16_t* __restrict__ hbuf,
-                                                           const int32_t* __restrict__ table, int H, int F,
-                                                           bf16_t* __restrict__ y) {
+                                                           const int32_t* __restrict__ table, int32_t* table_rw,
+                                                           int queue, int H, int F, bf16_t* __restrict__ y) {
 #if defined(__HIP_DEVICE_COMPILE__)
   extern __shared__ u32x4 smem[];
+  __shared__ int ticket;
+  const int n_tiles = table[0], n_cols = (H + FBN - 1) / FBN;
+  WorkQueue wq;
+  if (queue) wq.init(table_rw + kQueue2);
   int tile, col;
-  if (!ffn_work_item(table[0], (H + FBN - 1) / FBN, tile, col)) return;
-  const TileEntry e = reinterpret_cast<const TileEntry*>(table + 8)[tile];
-  const int n0 = col * FBN;
-  const bf16_t* w2 = static_cast<const bf16_t*>(e.w2);
-  if (e.height > 256)
-    gemm2_tile<5>(hbuf, w2, e.row0, e.rows, n0, H, F, y, smem);
-  else if (e.height > 192)
-    gemm2_tile<4>(hbuf, w2, e.row0, e.rows, n0, H, F, y, smem);
-  else if (e.height > 128)
-    gemm2_tile<3>(hbuf, w2, e.row0, e.rows, n0, H, F, y, smem);
-  else if (e.height > 64)
-    gemm2_tile<2>(hbuf, w2, e.row0, e.rows, n0, H, F, y, smem);
-  else
-    gemm2_tile<1>(hbuf, w2, e.row0, e.rows, n0, H, F, y, smem);
+  if (!queue && !ffn_work_item(n_tiles, n_cols, tile, col)) return;
+  while (!queue || wq.next(n_tiles, n_cols, &ticket, tile, col)) {
+    const TileEntry e = reinterpret_cast<const TileEntry*>(table + kTableHeaderInts)[tile];
+    const int n0 = col * FBN;
+    const bf16_t* w2 = static_cast<const bf16_t*>(e.w2);
+    if (e.height > 256)
+      gemm2_tile<5>(hbuf, w2, e.row0, e.rows, n0, H, F, y, smem);
+    else if (e.height > 192)
+      gemm2_tile<4>(hbuf, w2, e.row0, e.rows, n0, H, F, y, smem);
+    else if (e.height > 128)
+      gemm2_tile<3>(hbuf, w2, e.row0, e.rows, n0, H, F, y, smem);
+    else if (e.height > 64)
+      gemm2_tile<2>(hbuf, w2, e.row0, e.rows, n0, H, F, y, smem);
+    else
+      gemm2_tile<1>(hbuf, w2, e.row0, e.rows, n0, H, F, y, smem);
+    if (!queue) break;
+  }
 #endif
 }
 
@@ -432,7 +494,7 @@ __global__ __launch_bounds__(512, 4) void ffn_gemm1_skinny_kernel(RowSource src,
   const int n_cols = (F + kSkinnyCols1 - 1) / kSkinnyCols1;
   const int tile = blockIdx.x / n_cols, col = blockIdx.x % n_cols;
   if (tile >= table[0]) return;
-  const TileEntry e = reinterpret_cast<const TileEntry*>(table + 8)[tile];
+  const TileEntry e = reinterpret_cast<const TileEntry*>(table + kTableHeaderInts)[tile];
   gemm1_tile<1, GATHER, 1, 3>(src, static_cast<const bf16_t*>(e.w13), e.row0, e.rows, col * kSkinnyCols1, H, F, hbuf,
                               smem);
 #endif
@@ -446,7 +508,7 @@ __global__ __launch_bounds__(512, 4) void ffn_gemm2_skinny_kernel(const bf16_t* 
   const int n_cols = (H + kSkinnyCols2 - 1) / kSkinnyCols2;
   const int tile = blockIdx.x / n_cols, col = blockIdx.x % n_cols;
   if (tile >= table[0]) return;
-  const TileEntry e = reinterpret_cast<const TileEntry*>(table + 8)[tile];
+  const TileEntry e = reinterpret_cast<const TileEntry*>(table + kTableHeaderInts)[tile];
   gemm2_tile<1, 1, 3>(hbuf, static_cast<const bf16_t*>(e.w2), e.row0, e.rows, col * kSkinnyCols2, H, F, y, smem);
 #endif
 }
@@ -466,21 +528,32 @@ static FfnShape ffn_shape(int S, int F, int max_rows) {
   s.skinny = static_cast<long>(max_rows) <= static_cast<long>(kSkinnyRowsPerSlot) * S;
   s.max_tiles = s.skinny ? max_rows / 64 + S : max_rows / 256 + S;
   s.h_bytes = align_up(static_cast<size_t>(max_rows > 0 ? max_rows : 1) * F * sizeof(bf16_t), 256);
-  s.table_bytes = align_up((1 + static_cast<size_t>(s.max_tiles)) * sizeof(TileEntry), 256);
+  s.table_bytes = align_up(kTableHeaderInts * sizeof(int32_t) + static_cast<size_t>(s.max_tiles) * sizeof(TileEntry), 256);
   return s;
 }
 
-// The GEMM kernels use 144 KB of dynamic LDS, which has to be opted into once per device.
-static int ffn_prepare() {
+// The GEMM kernels use 144 KB of dynamic LDS, which has to be opted into once per device.  *cus receives
+// the device's CU count (the size of the persistent launch).
+static int ffn_prepare(int* cus) {
   static std::mutex mu;
   static bool done[64] = {false};
+  static int cu_count[64] = {0};
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
     set_error("probe_grouped_ffn: no current device");
     return PROBE_EHIP;
   }
   std::lock_guard<std::mutex> lock(mu);
-  if (done[dev]) return PROBE_OK;
+  if (done[dev]) {
+    *cus = cu_count[dev];
+    return PROBE_OK;
+  }
+  if (hipDeviceGetAttribute(&cu_count[dev], hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+      cu_count[dev] <= 0) {
+    set_error("probe_grouped_ffn: cannot read the CU count of device %d", dev);
+    return PROBE_EHIP;
+  }
+  *cus = cu_count[dev];
   hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(ffn_gemm1_kernel<false>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kFfnLdsBytes);
   if (err == hipSuccess)
@@ -548,7 +621,8 @@ static int ffn_impl(const char* name, const void* act_bf16, const int32_t* row_p
   PROBE_REQUIRE(static_cast<long>(sh.max_tiles + 8) * ((F + 127) / 128 + 4) < (1l << 30) &&
                     static_cast<long>(sh.max_tiles + 8) * ((H + 255) / 256 + 4) < (1l << 30),
                 PROBE_EUNSUPPORTED, "%s: max_rows too large (%d)", name, max_rows);
-  int rc = ffn_prepare();
+  int cus = 0;
+  int rc = ffn_prepare(&cus);
   if (rc != PROBE_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   bf16_t* hbuf = static_cast<bf16_t*>(workspace);
@@ -571,13 +645,17 @@ static int ffn_impl(const char* name, const void* act_bf16, const int32_t* row_p
                        static_cast<bf16_t*>(y_bf16));
     return check_launch(name);
   }
-  const dim3 grid1(ffn_grid(sh.max_tiles, (F + 127) / 128));
+  // persistent launch (one workgroup per CU, items drawn from the work queue) unless the capacity of the
+  // row space gives fewer items than that
+  const int cap1 = ffn_grid(sh.max_tiles, (F + 127) / 128), cap2 = ffn_grid(sh.max_tiles, (H + FBN - 1) / FBN);
+  const int q1 = cap1 > cus ? 1 : 0, q2 = cap2 > cus ? 1 : 0;
+  const dim3 grid1(q1 ? cus : cap1), grid2(q2 ? cus : cap2);
   if (gather)
-    hipLaunchKernelGGL(ffn_gemm1_kernel<true>, grid1, dim3(512), kFfnLdsBytes, st, src, table, H, F, hbuf);
+    hipLaunchKernelGGL(ffn_gemm1_kernel<true>, grid1, dim3(512), kFfnLdsBytes, st, src, table, table, q1, H, F, hbuf);
   else
-    hipLaunchKernelGGL(ffn_gemm1_kernel<false>, grid1, dim3(512), kFfnLdsBytes, st, src, table, H, F, hbuf);
-  hipLaunchKernelGGL(ffn_gemm2_kernel, dim3(ffn_grid(sh.max_tiles, (H + FBN - 1) / FBN)), dim3(512), kFfnLdsBytes, st,
-                     hbuf, table, H, F, static_cast<bf16_t*>(y_bf16));
+    hipLaunchKernelGGL(ffn_gemm1_kernel<false>, grid1, dim3(512), kFfnLdsBytes, st, src, table, table, q1, H, F, hbuf);
+  hipLaunchKernelGGL(ffn_gemm2_kernel, grid2, dim3(512), kFfnLdsBytes, st, hbuf, table, table, q2, H, F,
+                     static_cast<bf16_t*>(y_bf16));
   return check_launch(name);
 }
 
