@@ -26,10 +26,19 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E
-# L2-miss fetch + write bytes of ffn_gemm1 + ffn_gemm2 per call, from two rocprofv3 --pmc runs
-# (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0 after calibration on a plain 1 GiB copy kernel); the figures and
-# the commands are in profiles/bench_cfg3_hbm_traffic.md.  Only known for configuration 3.
-MEASURED_FFN_TRAFFIC_BYTES = {3: 7.17e9}
+
+
+def measured_ffn_traffic(cid):
+    """L2-miss fetch + write bytes of the FFN's two GEMM kernels per call, from the rocprofv3 --pmc summary
+    committed for this configuration (FETCH_SIZE / WRITE_SIZE scaled by a plain copy kernel; the figures and
+    the commands are in the file).  None if there is no summary for the configuration."""
+    import re
+    path = os.path.join(ROOT, "profiles", "bench_cfg%d_hbm_traffic.md" % cid)
+    try:
+        m = re.search(r"FFN_TRAFFIC_BYTES_PER_CALL\s*[:=]\s*([0-9.eE+]+)", open(path).read())
+    except OSError:
+        return None
+    return float(m.group(1)) if m else None
 
 
 def log(*a):
@@ -282,8 +291,11 @@ def main():
         "ffn_tflops": ffn_tflops,
         "ffn_frac_bf16_mfma_peak": ffn_tflops / PEAK_BF16_TFLOPS,
         "ffn_weight_stream_gbps": ffn_bytes / mean_ms["ffn"] / 1e6,
-        "stage_hbm_gbps": gbps,
-        "stage_frac_hbm_peak": {n: v / PEAK_HBM_GBPS for n, v in gbps.items()},
+        # algorithmic bytes of a stage over its time: rows just written by the previous stage are partly served by
+        # the 256 MB last-level cache, so these can exceed what a streaming copy reaches on the box
+        # (roofline.peak_measured) and are rates of algorithmic bytes, not proven HBM traffic
+        "stage_algorithmic_gbps": gbps,
+        "stage_algorithmic_frac_hbm_peak": {n: v / PEAK_HBM_GBPS for n, v in gbps.items()},
         # the gate is a contraction of 2*T*H*E flops that runs on the matrix cores as three bf16 planes (fp32
         # weights kept exact), so its arithmetic roof is the bf16 MFMA peak over plane-expanded flops; at E >= 128
         # that roof binds, at E = 8 the HBM one does
@@ -293,7 +305,7 @@ def main():
         "roofline": {"kernel": "probe_grouped_ffn (ffn_gemm1_kernel + ffn_gemm2_kernel)", "bound": "mfma",
                      "achieved": ffn_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": ffn_tflops / PEAK_BF16_TFLOPS,
-                     "traffic": MEASURED_FFN_TRAFFIC_BYTES.get(cfg.cid) if nb == min(cfg.n_batches, 8) else None,
+                     "traffic": measured_ffn_traffic(cfg.cid) if nb == min(cfg.n_batches, 8) else None,
                      "algorithmic_flops_per_launch": ffn_flops, "algorithmic_bytes_per_launch": ffn_bytes,
                      "launch_ms": mean_ms["ffn"]},
     }
@@ -342,6 +354,62 @@ def main():
                              "bottleneck_latency_after": st[1],
                              "imbalance_ratio_before": float(home_load.max()) / mean_load,
                              "imbalance_ratio_after": float(st[2]) / mean_load}
+
+    # The same step under a plan that was NOT built with hindsight: the lookahead predictor (this layer's cloned
+    # gate, Sec. 4.2) runs on drifted copies of the tokens that stand in for the previous layer's hidden states,
+    # its per-expert counts of the batch's eight token chunks (one chunk per virtual source rank, the all-gather
+    # of Sec. 4.2) go to the device planner (Algorithm 1), and the true router's pairs are permuted under that
+    # plan.  Set-up is untimed (the paper hides predictor and planner under the dispatch); what is timed is the
+    # main track, so the cost of a predicted plan shows as rows per step and step time.  Not part of `value`.
+    if 2 <= ep <= 16 and cfg.E_loc * ep == E and cfg.n_rep and T % ep == 0:
+        alpha = 0.5
+        kw = dict(max_replicas=cfg.n_rep, budget=3, k_max=16, n0=64, g_num=1, g_den=4)
+        chunk = T // ep
+        pl_plans, pl_tables, pl_rows, ir_pred, ir_hind = [], [], [], [], []
+        cnt = torch.empty((ep, E), dtype=torch.int32, device=dev)
+        for b in range(nb):
+            d_hp = dev_bf16(wl.drifted_activations(cfg, xs[b], alpha, b))
+            for r in range(ep):
+                sl = slice(r * chunk, (r + 1) * chunk)
+                # chunk r uses the bias rows of its own tokens
+                assert d_bias[b].shape[0] == 1 or (r * chunk) % tpg == 0
+                g0 = min((r * chunk) // tpg, d_bias[b].shape[0] - 1)
+                probe.predict_topk(d_hp[sl], g_route, d_bias[b][g0:], tpg, k, True,
+                                   out=dict(idx=p_out_pred["idx"][sl], w=p_out_pred["w"][sl], counts=cnt[r]),
+                                   workspace=ws_route)
+            pg = probe.plan_greedy(cnt, cfg.E_loc, rank=0, **kw)
+            se = pg["slot_expert"].cpu().numpy()
+            pl_plans.append(pg["plan"])
+            need2 = sorted({int(e) for e in se if e >= 0} - set(dev_w))
+            for e, w in zip(need2, wl.expert_weights_many(cfg, need2, threads=threads)):
+                dev_w[e] = (dev_bf16(w[0]), dev_bf16(w[1]))
+            pick = [int(e) if e >= 0 else 0 for e in se]          # an unused replica slot gets no rows
+            pl_tables.append(probe.WeightTable([dev_w[e][0] for e in pick], [dev_w[e][1] for e in pick]))
+            del d_hp
+        saved = (d_plans, tables)
+        d_plans, tables = pl_plans, pl_tables
+        S_pl = cfg.E_loc + cfg.n_rep
+        assert S_pl == S
+        for b in range(nb):
+            step(b)
+            pl_rows.append(int(perm_out["n_local"].item()))
+        torch.cuda.synchronize()
+        ev2 = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+        t_start = time.perf_counter()
+        for i in range(args.steps):
+            step(i % nb, ev2[i])
+        torch.cuda.synchronize()
+        el2 = time.perf_counter() - t_start
+        d_plans, tables = saved
+        st2 = {n: float(np.mean([ev2[i][j].elapsed_time(ev2[i][j + 1]) for i in range(args.steps)]))
+               for j, n in enumerate(names)}
+        rows2 = float(np.mean([pl_rows[i % nb] for i in range(args.steps)]))
+        result["predicted_plan"] = {
+            "what": "plan = probe_plan_greedy on probe_predict_topk counts of h_prev = drifted tokens (alpha %.1f), "
+                    "8 token chunks as source ranks; same step, same batches" % alpha,
+            "ms_per_step": el2 * 1e3 / args.steps, "tokens_per_s": T * args.steps / el2, "stage_ms": st2,
+            "rows_per_step_mean": rows2, "rows_per_step_mean_hindsight_plan": nl_mean,
+            "ffn_tflops": 6.0 * rows2 * H * F / (st2["ffn"] * 1e-3) / 1e12, "planner_params": kw}
 
     # the group-limited gate (sigmoid scores, E / 32 groups of 32 experts, half of them allowed) on the same
     # inputs, timed on its own next to the plain router; not part of `value`

@@ -23,12 +23,21 @@ _lock = threading.Lock()
 _lib = None
 
 
+# PROBE_ORACLE_SANITIZE=1 (set by oracle/run_sanitized.py for its child process) selects a second build of the
+# same sources with AddressSanitizer and UndefinedBehaviorSanitizer, kept in its own file.
+_SANITIZE = os.environ.get("PROBE_ORACLE_SANITIZE") == "1"
+if _SANITIZE:
+    _LIB = os.path.join(_HERE, "libprobe_oracle_san.so")
+
+
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (plain C99 + OpenMP).  Returns the library path."""
     stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < max(os.path.getmtime(f) for f in _SRCS)
     if force or stale:
         tmp = _LIB + ".tmp%d" % os.getpid()
-        cmd = ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-o", tmp] + _SRCS + ["-lm"]
+        flags = (["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined", "-fno-sanitize-recover=all"]
+                 if _SANITIZE else ["-O2"])
+        cmd = ["gcc"] + flags + ["-std=c99", "-fopenmp", "-fPIC", "-shared", "-o", tmp] + _SRCS + ["-lm"]
         subprocess.run(cmd, check=True)
         os.replace(tmp, _LIB)
     return _LIB

@@ -1,7 +1,7 @@
 """GPU parity: libprobe (HIP, through the C ABI) against the CPU oracle, stage by stage.
 
 Bars: integer outputs bit-exact (top-k indices wherever the oracle's order is unambiguous at
-1e-4 in the logits, otherwise a valid top-k within that margin); gate probabilities and
+1e-5 in the logits, otherwise a valid top-k within that margin); gate probabilities and
 weights within 1e-5 absolute; bf16 outputs within 2e-2 of the fp64 oracle in the metric
 max |g-o| / (|o| + rms(o))."""
 import json
@@ -73,11 +73,12 @@ def test_full_configs_every_element(oracle, probe, G, cid, batch):
 
 @pytest.mark.parametrize("cid,batch", [(2, 0), (3, 0), (3, 5), (5, 0)])
 def test_full_configs_sampled(oracle, probe, G, cid, batch):
-    """Full benchmark sizes: integer stages checked completely, floating-point stages on
-    sampled tokens / rows that the oracle computes one by one."""
+    """Full benchmark sizes: integer stages and the router (every token) checked completely; the FFN on a
+    stratified sample of about a thousand rows that reaches every row tile and every 32-row block of it, the
+    layer output on the tokens whose rows are all in the sample."""
     print("case sampled", cid, batch, flush=True)
-    G.run_layer_parity(oracle, probe, wl.CONFIGS[cid], batch=batch, route_sample=512, ffn_sample=48,
-                       seed=cid, report=REPORT)
+    G.run_layer_parity(oracle, probe, wl.CONFIGS[cid], batch=batch, route_sample=None,
+                       ffn_sample=320 if cid == 2 else 1024, seed=cid, report=REPORT)
     _flush_report()
 
 
