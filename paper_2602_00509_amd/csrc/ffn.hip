@@ -69,19 +69,14 @@ constexpr int kTableHeaderInts = 32, kQueue1 = 8, kQueue2 = 16;
 constexpr bool kInterleave = true;
 
 struct SlotCut {
-  int n320, n256, n64, tail;  // tail = height of the one short tile (64, 128 or 192), 0 if there is none
-  __device__ __forceinline__ int tiles() const { return n320 + n256 + n64 + (tail ? 1 : 0); }
+  int n320, n256, tail;  // tail = height of the one short tile (64, 128 or 192), 0 if there is none
+  __device__ __forceinline__ int tiles() const { return n320 + n256 + (tail ? 1 : 0); }
 };
 
-// skinny = the decode schedule: every tile is 64 rows high (see ffn_gemm1_skinny_kernel)
-__device__ __forceinline__ SlotCut cut_slot(int m, bool skinny) {
-  SlotCut c = {0, 0, 0, 0};
+__device__ __forceinline__ SlotCut cut_slot(int m) {
+  SlotCut c = {0, 0, 0};
   const int u = (m + 63) >> 6;
   if (u == 0) return c;
-  if (skinny) {
-    c.n64 = u;
-    return c;
-  }
   if (u <= 3) {
     c.tail = 64 * u;
     return c;
@@ -101,7 +96,7 @@ __device__ __forceinline__ SlotCut cut_slot(int m, bool skinny) {
 __global__ __launch_bounds__(256) void ffn_schedule_kernel(const int32_t* __restrict__ slot_offsets,
                                                            const void* const* __restrict__ w13_ptrs,
                                                            const void* const* __restrict__ w2_ptrs,
-                                                           int S, int max_tiles, int skinny,
+                                                           int S, int max_tiles,
                                                            int32_t* __restrict__ table) {
   __shared__ int32_t rows_of[PROBE_MAX_SLOTS];
   __shared__ int32_t first_of[PROBE_MAX_SLOTS];
@@ -142,7 +137,7 @@ __global__ __launch_bounds__(256) void ffn_schedule_kernel(const int32_t* __rest
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int p = tid * 4 + i;
-    v[i] = p < S ? cut_slot(rows_of[slot_at[p]], skinny != 0).tiles() : 0;
+    v[i] = p < S ? cut_slot(rows_of[slot_at[p]]).tiles() : 0;
     local += v[i];
   }
   int incl = local;
@@ -186,7 +181,7 @@ __global__ __launch_bounds__(256) void ffn_schedule_kernel(const int32_t* __rest
       if (start[mid] <= t) lo = mid; else hi = mid;
     }
     const int slot = slot_at[lo], first = first_of[slot];
-    const SlotCut c = cut_slot(rows_of[slot], skinny != 0);
+    const SlotCut c = cut_slot(rows_of[slot]);
     int i = t - start[lo], row0 = first, height;
     if (i < c.n320) {
       row0 += i * 320;
@@ -194,11 +189,8 @@ __global__ __launch_bounds__(256) void ffn_schedule_kernel(const int32_t* __rest
     } else if ((i -= c.n320) < c.n256) {
       row0 += c.n320 * 320 + i * 256;
       height = 256;
-    } else if ((i -= c.n256) < c.n64) {
-      row0 += c.n320 * 320 + c.n256 * 256 + i * 64;
-      height = 64;
     } else {
-      row0 += c.n320 * 320 + c.n256 * 256 + c.n64 * 64;
+      row0 += c.n320 * 320 + c.n256 * 256;
       height = c.tail;
     }
     TileEntry e;
@@ -486,30 +478,92 @@ __global__ __launch_bounds__(512, 2) void ffn_gemm2_kernel(const bf16_t* __restr
 constexpr int kSkinnyLdsBytes = 3 * (64 + 128) * 128;  // 72 KB
 constexpr int kSkinnyCols1 = 64, kSkinnyCols2 = 128;   // h columns / y columns per work item
 
+// Tile number -> (slot, first row, rows to the end of the slot, weight pointer) without a tile table: slots
+// in their own order, ceil(M / 64) tiles each.  Every workgroup finds its own tile with one scan over the
+// (at most 1024) slots, two per thread, so the decode schedule needs no schedule kernel in front of it.
+// Returns false if the tile number is past the last tile (the launch is sized for the capacity).
+struct SkinnyTile {
+  int row0, rows;
+  const void* w;
+};
+
+__device__ __forceinline__ bool skinny_locate(const int32_t* __restrict__ slot_offsets,
+                                              const void* const* __restrict__ w_ptrs, int S, int tile,
+                                              SkinnyTile& out) {
+  __shared__ int32_t wave_tot[8];
+  __shared__ int32_t found_row0, found_rows;
+  __shared__ const void* found_w;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  if (tid == 0) found_rows = 0;
+  int first[2], m[2], t[2];
+  const void* w[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int sl = 2 * tid + i;
+    first[i] = m[i] = 0;
+    w[i] = nullptr;
+    if (sl < S) {
+      first[i] = slot_offsets[sl];
+      m[i] = max(slot_offsets[sl + 1] - first[i], 0);
+      w[i] = w_ptrs[sl];
+    }
+    t[i] = (m[i] + 63) >> 6;
+  }
+  const int local = t[0] + t[1];
+  int incl = local;
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    int o = __shfl_up(incl, d, kWave);
+    if (lane >= d) incl += o;
+  }
+  if (lane == kWave - 1) wave_tot[wv] = incl;
+  __syncthreads();
+  int excl = incl - local;
+  for (int i = 0; i < wv; ++i) excl += wave_tot[i];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    if (tile >= excl && tile < excl + t[i]) {  // true for exactly one (thread, i) when the tile exists
+      const int r = (tile - excl) * 64;
+      found_row0 = first[i] + r;
+      found_rows = m[i] - r;
+      found_w = w[i];
+    }
+    excl += t[i];
+  }
+  __syncthreads();
+  out.row0 = found_row0;
+  out.rows = found_rows;
+  out.w = found_w;
+  return found_rows > 0;
+}
+
 template <bool GATHER>
-__global__ __launch_bounds__(512, 4) void ffn_gemm1_skinny_kernel(RowSource src, const int32_t* __restrict__ table,
+__global__ __launch_bounds__(512, 4) void ffn_gemm1_skinny_kernel(RowSource src,
+                                                                  const int32_t* __restrict__ slot_offsets,
+                                                                  const void* const* __restrict__ w13_ptrs, int S,
                                                                   int H, int F, bf16_t* __restrict__ hbuf) {
 #if defined(__HIP_DEVICE_COMPILE__)
   extern __shared__ u32x4 smem[];
   const int n_cols = (F + kSkinnyCols1 - 1) / kSkinnyCols1;
   const int tile = blockIdx.x / n_cols, col = blockIdx.x % n_cols;
-  if (tile >= table[0]) return;
-  const TileEntry e = reinterpret_cast<const TileEntry*>(table + kTableHeaderInts)[tile];
-  gemm1_tile<1, GATHER, 1, 3>(src, static_cast<const bf16_t*>(e.w13), e.row0, e.rows, col * kSkinnyCols1, H, F, hbuf,
+  SkinnyTile e;
+  if (!skinny_locate(slot_offsets, w13_ptrs, S, tile, e)) return;
+  gemm1_tile<1, GATHER, 1, 3>(src, static_cast<const bf16_t*>(e.w), e.row0, e.rows, col * kSkinnyCols1, H, F, hbuf,
                               smem);
 #endif
 }
 
 __global__ __launch_bounds__(512, 4) void ffn_gemm2_skinny_kernel(const bf16_t* __restrict__ hbuf,
-                                                                  const int32_t* __restrict__ table, int H, int F,
-                                                                  bf16_t* __restrict__ y) {
+                                                                  const int32_t* __restrict__ slot_offsets,
+                                                                  const void* const* __restrict__ w2_ptrs, int S,
+                                                                  int H, int F, bf16_t* __restrict__ y) {
 #if defined(__HIP_DEVICE_COMPILE__)
   extern __shared__ u32x4 smem[];
   const int n_cols = (H + kSkinnyCols2 - 1) / kSkinnyCols2;
   const int tile = blockIdx.x / n_cols, col = blockIdx.x % n_cols;
-  if (tile >= table[0]) return;
-  const TileEntry e = reinterpret_cast<const TileEntry*>(table + kTableHeaderInts)[tile];
-  gemm2_tile<1, 1, 3>(hbuf, static_cast<const bf16_t*>(e.w2), e.row0, e.rows, col * kSkinnyCols2, H, F, y, smem);
+  SkinnyTile e;
+  if (!skinny_locate(slot_offsets, w2_ptrs, S, tile, e)) return;
+  gemm2_tile<1, 1, 3>(hbuf, static_cast<const bf16_t*>(e.w), e.row0, e.rows, col * kSkinnyCols2, H, F, y, smem);
 #endif
 }
 
@@ -627,8 +681,6 @@ static int ffn_impl(const char* name, const void* act_bf16, const int32_t* row_p
   hipStream_t st = static_cast<hipStream_t>(stream);
   bf16_t* hbuf = static_cast<bf16_t*>(workspace);
   int32_t* table = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + sh.h_bytes);
-  hipLaunchKernelGGL(ffn_schedule_kernel, dim3(1), dim3(256), 0, st, slot_offsets, w13_ptrs, w2_ptrs, S, sh.max_tiles,
-                     sh.skinny ? 1 : 0, table);
   RowSource src;
   src.base = static_cast<const bf16_t*>(act_bf16);
   src.row_pair = row_pair;
@@ -638,13 +690,17 @@ static int ffn_impl(const char* name, const void* act_bf16, const int32_t* row_p
     const dim3 g1(sh.max_tiles * ((F + kSkinnyCols1 - 1) / kSkinnyCols1));
     const dim3 g2(sh.max_tiles * ((H + kSkinnyCols2 - 1) / kSkinnyCols2));
     if (gather)
-      hipLaunchKernelGGL(ffn_gemm1_skinny_kernel<true>, g1, dim3(512), kSkinnyLdsBytes, st, src, table, H, F, hbuf);
+      hipLaunchKernelGGL(ffn_gemm1_skinny_kernel<true>, g1, dim3(512), kSkinnyLdsBytes, st, src, slot_offsets,
+                         w13_ptrs, S, H, F, hbuf);
     else
-      hipLaunchKernelGGL(ffn_gemm1_skinny_kernel<false>, g1, dim3(512), kSkinnyLdsBytes, st, src, table, H, F, hbuf);
-    hipLaunchKernelGGL(ffn_gemm2_skinny_kernel, g2, dim3(512), kSkinnyLdsBytes, st, hbuf, table, H, F,
-                       static_cast<bf16_t*>(y_bf16));
+      hipLaunchKernelGGL(ffn_gemm1_skinny_kernel<false>, g1, dim3(512), kSkinnyLdsBytes, st, src, slot_offsets,
+                         w13_ptrs, S, H, F, hbuf);
+    hipLaunchKernelGGL(ffn_gemm2_skinny_kernel, g2, dim3(512), kSkinnyLdsBytes, st, hbuf, slot_offsets, w2_ptrs, S, H,
+                       F, static_cast<bf16_t*>(y_bf16));
     return check_launch(name);
   }
+  hipLaunchKernelGGL(ffn_schedule_kernel, dim3(1), dim3(256), 0, st, slot_offsets, w13_ptrs, w2_ptrs, S, sh.max_tiles,
+                     table);
   // persistent launch (one workgroup per CU, items drawn from the work queue) unless the capacity of the
   // row space gives fewer items than that
   const int cap1 = ffn_grid(sh.max_tiles, (F + 127) / 128), cap2 = ffn_grid(sh.max_tiles, (H + FBN - 1) / FBN);

@@ -323,7 +323,7 @@ __device__ __forceinline__ int tree_min(const int (&v)[N]) {
 
 // Logit row pieces of U tokens: the KS split-K slices are added in ascending order, then the bias row
 // of the token's group.  Lane `sub` receives the experts 64*i + 4*sub + j; entries past E are zero.
-template <int NV, int U>
+template <int NV, int U, int R = 2>
 __device__ __forceinline__ void load_logit_rows(const float* __restrict__ partial, int ld, int KS,
                                                 const float* __restrict__ bias, int G, int tpg, int T, int E,
                                                 bool vec, int sub, const int (&tt)[U], float (&l)[U][NV * 4]) {
@@ -334,11 +334,11 @@ __device__ __forceinline__ void load_logit_rows(const float* __restrict__ partia
     for (int u = 0; u < U; ++u)
 #pragma unroll
       for (int i = 0; i < NV; ++i) accv[u][i] = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int q0 = 0; q0 < KS; q0 += 2) {
-      // all loads of a round of two split-K slices (of both tokens) are issued before any is consumed
-      float4 tmp[2][U][NV];
+    for (int q0 = 0; q0 < KS; q0 += R) {
+      // all loads of a round of R split-K slices (of every token of the row) are issued before any is consumed
+      float4 tmp[R][U][NV];
 #pragma unroll
-      for (int r = 0; r < 2; ++r) {
+      for (int r = 0; r < R; ++r) {
         const int q = min(q0 + r, KS - 1);
 #pragma unroll
         for (int u = 0; u < U; ++u)
@@ -349,7 +349,7 @@ __device__ __forceinline__ void load_logit_rows(const float* __restrict__ partia
           }
       }
 #pragma unroll
-      for (int r = 0; r < 2; ++r)
+      for (int r = 0; r < R; ++r)
         if (q0 + r < KS) {
 #pragma unroll
           for (int u = 0; u < U; ++u)
@@ -398,13 +398,13 @@ __device__ __forceinline__ void load_logit_rows(const float* __restrict__ partia
 // other's.  A chosen logit is overwritten with -inf; incoming logits are clamped to >= -FLT_MAX
 // (NaN too), so -inf only ever means "taken".  The weight of a winner is recomputed from its
 // logit with the same expression as its probability, so both agree bit for bit.
-template <int NV>
+template <int NV, int U = 2, int R = 2>
 __global__ __launch_bounds__(256) void gate_softmax_topk_kernel(
     const float* __restrict__ partial, int ld, int KS, const float* __restrict__ bias, int G, int tpg, int T,
     int E, int k, int renorm, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
     float* __restrict__ probs, int32_t* __restrict__ counts) {
   // `partial` points at this gate's first column; a row of a partial plane has ld entries
-  constexpr int U = 2, NL = NV * 4;
+  constexpr int NL = NV * 4;
   __shared__ int32_t hist[PROBE_MAX_EXPERTS];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int sub = lane & 15, grp = lane >> 4;
@@ -423,7 +423,7 @@ __global__ __launch_bounds__(256) void gate_softmax_topk_kernel(
       live[u] = t0 + 4 * u < T;
       tt[u] = live[u] ? t0 + 4 * u : t0;
     }
-    load_logit_rows<NV, U>(partial, ld, KS, bias, G, tpg, T, E, vec, sub, tt, l);
+    load_logit_rows<NV, U, R>(partial, ld, KS, bias, G, tpg, T, E, vec, sub, tt, l);
     float mx[U], inv[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -994,10 +994,21 @@ static int route_impl(const char* name, const void* x_bf16, const float* w_gate,
       }
     } else if (E <= 64) {
       PROBE_TOPK_LAUNCH(1);
-    } else if (E <= 128) {
-      PROBE_TOPK_LAUNCH(2);
     } else {
-      PROBE_TOPK_LAUNCH(4);
+      // small batches (decode): one token per row in flight and all split-K slices loaded at once give twice
+      // the waves per SIMD to hide the loads behind; large batches are bound by reading the partial sums
+      // either way (measured at 8192 and 16384 tokens: no difference)
+#define PROBE_TOPK_LAUNCH_SMALL(V)                                                                              \
+  hipLaunchKernelGGL((gate_softmax_topk_kernel<V, 1, 4>), dim3((T + 15) / 16), dim3(256), 0, st, partial, E,     \
+                     planes_to_sum, bias, G, tpg, T, E, k, renormalize ? 1 : 0, topk_idx, topk_w, probs,        \
+                     expert_counts)
+      const bool small = T <= 2048;
+      if (E <= 128) {
+        if (small) PROBE_TOPK_LAUNCH_SMALL(2); else PROBE_TOPK_LAUNCH(2);
+      } else {
+        if (small) PROBE_TOPK_LAUNCH_SMALL(4); else PROBE_TOPK_LAUNCH(4);
+      }
+#undef PROBE_TOPK_LAUNCH_SMALL
     }
 #undef PROBE_TOPK_LAUNCH
 #undef PROBE_GROUPED_LAUNCH
