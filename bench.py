@@ -67,6 +67,10 @@ def main():
                     help="hand the router and the predictor the fp32 gate matrices, which they split into bf16 planes "
                          "on every call (default: planes made once by probe_pack_gate, untimed set-up whose cost is "
                          "reported as gate_pack_us)")
+    ap.add_argument("--main-only", action="store_true",
+                    help="only the timed step: no measured peaks, predictor overlap, planner, group-limited gate or "
+                         "predicted-plan sections and no CPU baseline (for profiler runs, so that a kernel's average "
+                         "in the trace is its average over the step's launches)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -310,129 +314,130 @@ def main():
                      "launch_ms": mean_ms["ffn"]},
     }
 
-    # what this machine sustains, next to the nominal peaks: MFMA-only loop (no memory instruction) with zero
-    # and with random bf16 operands, and a plain streaming copy
-    result["roofline"]["peak_measured"] = measure_peaks(torch, dev)
-    result["roofline"]["frac_of_measured_mfma_random"] = (
-        ffn_tflops / result["roofline"]["peak_measured"]["mfma_only_random_operands_tflops"])
+    if not args.main_only:
+        # what this machine sustains, next to the nominal peaks: MFMA-only loop (no memory instruction) with zero
+        # and with random bf16 operands, and a plain streaming copy
+        result["roofline"]["peak_measured"] = measure_peaks(torch, dev)
+        result["roofline"]["frac_of_measured_mfma_random"] = (
+            ffn_tflops / result["roofline"]["peak_measured"]["mfma_only_random_operands_tflops"])
 
-    # the predictor's top-k accuracy: the cloned gate of the next layer on this layer's hidden states against
-    # the same gate on the next layer's hidden states (drifted copies of batch 0; two drift levels)
-    ov = {}
-    for alpha in (0.2, 0.5):
-        d_xn = dev_bf16(wl.drifted_activations(cfg, xs[0], alpha, 0))
-        pr = probe.predict_topk(d_xs[0], d_wg_next, d_bias_next[0], tpg, k, True)
-        tr = probe.route_topk(d_xn, d_wg_next, d_bias_next[0], tpg, k, True)
-        hits, _ = probe.predictor_metrics(pr["idx"], tr["idx"])
-        ov["drift_%.1f" % alpha] = int(hits.item()) / float(T * k)
-        del d_xn
-    result["predictor_topk_overlap"] = ov
+        # the predictor's top-k accuracy: the cloned gate of the next layer on this layer's hidden states against
+        # the same gate on the next layer's hidden states (drifted copies of batch 0; two drift levels)
+        ov = {}
+        for alpha in (0.2, 0.5):
+            d_xn = dev_bf16(wl.drifted_activations(cfg, xs[0], alpha, 0))
+            pr = probe.predict_topk(d_xs[0], d_wg_next, d_bias_next[0], tpg, k, True)
+            tr = probe.route_topk(d_xn, d_wg_next, d_bias_next[0], tpg, k, True)
+            hits, _ = probe.predictor_metrics(pr["idx"], tr["idx"])
+            ov["drift_%.1f" % alpha] = int(hits.item()) / float(T * k)
+            del d_xn
+        result["predictor_topk_overlap"] = ov
 
-    # the greedy planner (Algorithm 1) on the device, timed on its own: the batches stand in for the source
-    # ranks whose predicted counts an all-gather would deliver; not part of `value`
-    ep = cfg.E // cfg.E_loc
-    if 2 <= ep <= 16 and cfg.E_loc * ep == E:
-        rows = [all_counts[r % nb] for r in range(ep)]
-        d_nhat = torch.from_numpy(np.stack(rows).astype(np.int32)).to(dev)
-        kw = dict(max_replicas=cfg.n_rep if cfg.n_rep else 3, budget=3, k_max=16, n0=64, g_num=1, g_den=4)
-        for _ in range(3):
-            pl = probe.plan_greedy(d_nhat, cfg.E_loc, rank=0, **kw)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(20):
-            pl = probe.plan_greedy(d_nhat, cfg.E_loc, rank=0, **kw)
-        e1.record()
-        torch.cuda.synchronize()
-        st = pl["stats"].cpu().tolist()
-        # Eq. 1 on token loads: before = every expert at home, after = the plan's assignment
-        per_expert = np.stack(rows).astype(np.int64).sum(0)
-        home_load = per_expert.reshape(ep, cfg.E_loc).sum(1)
-        mean_load = float(per_expert.sum()) / ep
-        result["planner"] = {"us_per_call": e0.elapsed_time(e1) * 1e3 / 20, "ranks": ep, "experts": E,
-                             "params": kw, "moves": st[3], "bottleneck_latency_before": st[0],
-                             "bottleneck_latency_after": st[1],
-                             "imbalance_ratio_before": float(home_load.max()) / mean_load,
-                             "imbalance_ratio_after": float(st[2]) / mean_load}
-
-    # The same step under a plan that was NOT built with hindsight: the lookahead predictor (this layer's cloned
-    # gate, Sec. 4.2) runs on drifted copies of the tokens that stand in for the previous layer's hidden states,
-    # its per-expert counts of the batch's eight token chunks (one chunk per virtual source rank, the all-gather
-    # of Sec. 4.2) go to the device planner (Algorithm 1), and the true router's pairs are permuted under that
-    # plan.  Set-up is untimed (the paper hides predictor and planner under the dispatch); what is timed is the
-    # main track, so the cost of a predicted plan shows as rows per step and step time.  Not part of `value`.
-    if 2 <= ep <= 16 and cfg.E_loc * ep == E and cfg.n_rep and T % ep == 0:
-        alpha = 0.5
-        kw = dict(max_replicas=cfg.n_rep, budget=3, k_max=16, n0=64, g_num=1, g_den=4)
-        chunk = T // ep
-        pl_plans, pl_tables, pl_rows, ir_pred, ir_hind = [], [], [], [], []
-        cnt = torch.empty((ep, E), dtype=torch.int32, device=dev)
-        for b in range(nb):
-            d_hp = dev_bf16(wl.drifted_activations(cfg, xs[b], alpha, b))
-            for r in range(ep):
-                sl = slice(r * chunk, (r + 1) * chunk)
-                # chunk r uses the bias rows of its own tokens
-                assert d_bias[b].shape[0] == 1 or (r * chunk) % tpg == 0
-                g0 = min((r * chunk) // tpg, d_bias[b].shape[0] - 1)
-                probe.predict_topk(d_hp[sl], g_route, d_bias[b][g0:], tpg, k, True,
-                                   out=dict(idx=p_out_pred["idx"][sl], w=p_out_pred["w"][sl], counts=cnt[r]),
-                                   workspace=ws_route)
-            pg = probe.plan_greedy(cnt, cfg.E_loc, rank=0, **kw)
-            se = pg["slot_expert"].cpu().numpy()
-            pl_plans.append(pg["plan"])
-            need2 = sorted({int(e) for e in se if e >= 0} - set(dev_w))
-            for e, w in zip(need2, wl.expert_weights_many(cfg, need2, threads=threads)):
-                dev_w[e] = (dev_bf16(w[0]), dev_bf16(w[1]))
-            pick = [int(e) if e >= 0 else 0 for e in se]          # an unused replica slot gets no rows
-            pl_tables.append(probe.WeightTable([dev_w[e][0] for e in pick], [dev_w[e][1] for e in pick]))
-            del d_hp
-        saved = (d_plans, tables)
-        d_plans, tables = pl_plans, pl_tables
-        S_pl = cfg.E_loc + cfg.n_rep
-        assert S_pl == S
-        for b in range(nb):
-            step(b)
-            pl_rows.append(int(perm_out["n_local"].item()))
-        torch.cuda.synchronize()
-        ev2 = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
-        t_start = time.perf_counter()
-        for i in range(args.steps):
-            step(i % nb, ev2[i])
-        torch.cuda.synchronize()
-        el2 = time.perf_counter() - t_start
-        d_plans, tables = saved
-        st2 = {n: float(np.mean([ev2[i][j].elapsed_time(ev2[i][j + 1]) for i in range(args.steps)]))
-               for j, n in enumerate(names)}
-        rows2 = float(np.mean([pl_rows[i % nb] for i in range(args.steps)]))
-        result["predicted_plan"] = {
-            "what": "plan = probe_plan_greedy on probe_predict_topk counts of h_prev = drifted tokens (alpha %.1f), "
-                    "8 token chunks as source ranks; same step, same batches" % alpha,
-            "ms_per_step": el2 * 1e3 / args.steps, "tokens_per_s": T * args.steps / el2, "stage_ms": st2,
-            "rows_per_step_mean": rows2, "rows_per_step_mean_hindsight_plan": nl_mean,
-            "ffn_tflops": 6.0 * rows2 * H * F / (st2["ffn"] * 1e-3) / 1e12, "planner_params": kw}
-
-    # the group-limited gate (sigmoid scores, E / 32 groups of 32 experts, half of them allowed) on the same
-    # inputs, timed on its own next to the plain router; not part of `value`
-    if E % 32 == 0 and E >= 64:
-        ng = E // 32
-        gkw = dict(scoring="sigmoid", n_group=ng, topk_group=max(ng // 2, 1), group_top=2, k=k, renormalize=True,
-                   routed_scale=2.5)
-        d_sb = torch.zeros((E,), dtype=torch.float32, device=dev)
-        times = {}
-        for name, fn in (("route_topk", lambda: probe.route_topk(d_xs[0], d_wg, d_bias[0], tpg, k, True, workspace=ws_route)),
-                         ("route_grouped", lambda: probe.route_grouped(d_xs[0], d_wg, d_bias[0], tpg, d_sb, workspace=ws_route, **gkw))):
+        # the greedy planner (Algorithm 1) on the device, timed on its own: the batches stand in for the source
+        # ranks whose predicted counts an all-gather would deliver; not part of `value`
+        ep = cfg.E // cfg.E_loc
+        if 2 <= ep <= 16 and cfg.E_loc * ep == E:
+            rows = [all_counts[r % nb] for r in range(ep)]
+            d_nhat = torch.from_numpy(np.stack(rows).astype(np.int32)).to(dev)
+            kw = dict(max_replicas=cfg.n_rep if cfg.n_rep else 3, budget=3, k_max=16, n0=64, g_num=1, g_den=4)
             for _ in range(3):
-                fn()
+                pl = probe.plan_greedy(d_nhat, cfg.E_loc, rank=0, **kw)
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             for _ in range(20):
-                fn()
+                pl = probe.plan_greedy(d_nhat, cfg.E_loc, rank=0, **kw)
             e1.record()
             torch.cuda.synchronize()
-            times[name] = e0.elapsed_time(e1) * 1e3 / 20
-        result["grouped_gate"] = {"us_per_call": times["route_grouped"], "plain_router_us_per_call": times["route_topk"],
-                                  "n_group": ng, "topk_group": gkw["topk_group"], "scoring": "sigmoid"}
+            st = pl["stats"].cpu().tolist()
+            # Eq. 1 on token loads: before = every expert at home, after = the plan's assignment
+            per_expert = np.stack(rows).astype(np.int64).sum(0)
+            home_load = per_expert.reshape(ep, cfg.E_loc).sum(1)
+            mean_load = float(per_expert.sum()) / ep
+            result["planner"] = {"us_per_call": e0.elapsed_time(e1) * 1e3 / 20, "ranks": ep, "experts": E,
+                                 "params": kw, "moves": st[3], "bottleneck_latency_before": st[0],
+                                 "bottleneck_latency_after": st[1],
+                                 "imbalance_ratio_before": float(home_load.max()) / mean_load,
+                                 "imbalance_ratio_after": float(st[2]) / mean_load}
+
+        # The same step under a plan that was NOT built with hindsight: the lookahead predictor (this layer's cloned
+        # gate, Sec. 4.2) runs on drifted copies of the tokens that stand in for the previous layer's hidden states,
+        # its per-expert counts of the batch's eight token chunks (one chunk per virtual source rank, the all-gather
+        # of Sec. 4.2) go to the device planner (Algorithm 1), and the true router's pairs are permuted under that
+        # plan.  Set-up is untimed (the paper hides predictor and planner under the dispatch); what is timed is the
+        # main track, so the cost of a predicted plan shows as rows per step and step time.  Not part of `value`.
+        if 2 <= ep <= 16 and cfg.E_loc * ep == E and cfg.n_rep and T % ep == 0:
+            alpha = 0.5
+            kw = dict(max_replicas=cfg.n_rep, budget=3, k_max=16, n0=64, g_num=1, g_den=4)
+            chunk = T // ep
+            pl_plans, pl_tables, pl_rows, ir_pred, ir_hind = [], [], [], [], []
+            cnt = torch.empty((ep, E), dtype=torch.int32, device=dev)
+            for b in range(nb):
+                d_hp = dev_bf16(wl.drifted_activations(cfg, xs[b], alpha, b))
+                for r in range(ep):
+                    sl = slice(r * chunk, (r + 1) * chunk)
+                    # chunk r uses the bias rows of its own tokens
+                    assert d_bias[b].shape[0] == 1 or (r * chunk) % tpg == 0
+                    g0 = min((r * chunk) // tpg, d_bias[b].shape[0] - 1)
+                    probe.predict_topk(d_hp[sl], g_route, d_bias[b][g0:], tpg, k, True,
+                                       out=dict(idx=p_out_pred["idx"][sl], w=p_out_pred["w"][sl], counts=cnt[r]),
+                                       workspace=ws_route)
+                pg = probe.plan_greedy(cnt, cfg.E_loc, rank=0, **kw)
+                se = pg["slot_expert"].cpu().numpy()
+                pl_plans.append(pg["plan"])
+                need2 = sorted({int(e) for e in se if e >= 0} - set(dev_w))
+                for e, w in zip(need2, wl.expert_weights_many(cfg, need2, threads=threads)):
+                    dev_w[e] = (dev_bf16(w[0]), dev_bf16(w[1]))
+                pick = [int(e) if e >= 0 else 0 for e in se]          # an unused replica slot gets no rows
+                pl_tables.append(probe.WeightTable([dev_w[e][0] for e in pick], [dev_w[e][1] for e in pick]))
+                del d_hp
+            saved = (d_plans, tables)
+            d_plans, tables = pl_plans, pl_tables
+            S_pl = cfg.E_loc + cfg.n_rep
+            assert S_pl == S
+            for b in range(nb):
+                step(b)
+                pl_rows.append(int(perm_out["n_local"].item()))
+            torch.cuda.synchronize()
+            ev2 = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+            t_start = time.perf_counter()
+            for i in range(args.steps):
+                step(i % nb, ev2[i])
+            torch.cuda.synchronize()
+            el2 = time.perf_counter() - t_start
+            d_plans, tables = saved
+            st2 = {n: float(np.mean([ev2[i][j].elapsed_time(ev2[i][j + 1]) for i in range(args.steps)]))
+                   for j, n in enumerate(names)}
+            rows2 = float(np.mean([pl_rows[i % nb] for i in range(args.steps)]))
+            result["predicted_plan"] = {
+                "what": "plan = probe_plan_greedy on probe_predict_topk counts of h_prev = drifted tokens (alpha %.1f), "
+                        "8 token chunks as source ranks; same step, same batches" % alpha,
+                "ms_per_step": el2 * 1e3 / args.steps, "tokens_per_s": T * args.steps / el2, "stage_ms": st2,
+                "rows_per_step_mean": rows2, "rows_per_step_mean_hindsight_plan": nl_mean,
+                "ffn_tflops": 6.0 * rows2 * H * F / (st2["ffn"] * 1e-3) / 1e12, "planner_params": kw}
+
+        # the group-limited gate (sigmoid scores, E / 32 groups of 32 experts, half of them allowed) on the same
+        # inputs, timed on its own next to the plain router; not part of `value`
+        if E % 32 == 0 and E >= 64:
+            ng = E // 32
+            gkw = dict(scoring="sigmoid", n_group=ng, topk_group=max(ng // 2, 1), group_top=2, k=k, renormalize=True,
+                       routed_scale=2.5)
+            d_sb = torch.zeros((E,), dtype=torch.float32, device=dev)
+            times = {}
+            for name, fn in (("route_topk", lambda: probe.route_topk(d_xs[0], d_wg, d_bias[0], tpg, k, True, workspace=ws_route)),
+                             ("route_grouped", lambda: probe.route_grouped(d_xs[0], d_wg, d_bias[0], tpg, d_sb, workspace=ws_route, **gkw))):
+                for _ in range(3):
+                    fn()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(20):
+                    fn()
+                e1.record()
+                torch.cuda.synchronize()
+                times[name] = e0.elapsed_time(e1) * 1e3 / 20
+            result["grouped_gate"] = {"us_per_call": times["route_grouped"], "plain_router_us_per_call": times["route_topk"],
+                                      "n_group": ng, "topk_group": gkw["topk_group"], "scoring": "sigmoid"}
 
     if args.calibrate_copy:
         src = torch.ones((1 << 28,), dtype=torch.float32, device=dev)      # 1 GiB
@@ -442,7 +447,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.main_only:
         result["cpu_baseline"] = cpu_baseline(cfg, xs[0], wg, biases[0], tpg, plans[0], host_w, slot_experts[0],
                                               args.cpu_sample_tokens)
     print(json.dumps(result), flush=True)

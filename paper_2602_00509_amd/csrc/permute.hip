@@ -6,17 +6,18 @@
 //
 //   1. hist     each workgroup counts the experts of its own contiguous block of 1024 pairs
 //               (wave ballots, LDS counters)                             -> blk_hist[U][E]
-//   2. scan     per expert, exclusive scan over blocks                   -> blk_hist becomes
-//               blk_base; n_e; closed-form rows per replica; prefix sum over slots
-//               -> slot_counts, slot_offsets, n_local
-//   3. index    every workgroup re-walks its block (each wave a 256-pair segment, bases of the
-//               later waves from the earlier waves' counts), ranks each pair among equal
-//               experts with wave ballots, computes slot and row analytically -> pair_row, row_pair
-//   4. scatter  one thread per 16-byte chunk of a token row: read x once, write it to each of
+//   2. index    every workgroup sums the block histograms (its exclusive base = the blocks before it,
+//               n_e = all blocks), derives the rows per replica in closed form and the prefix sum over
+//               slots (workgroup 0 writes slot_counts, slot_offsets, n_local), then re-walks its block
+//               (each wave a 256-pair segment, bases of the later waves from the earlier waves' counts),
+//               ranks each pair among equal experts with wave ballots and computes slot and row
+//               analytically                                             -> pair_row, row_pair
+//   3. scatter  one thread per 16-byte chunk of a token row: read x once, write it to each of
 //               the token's local rows                                   -> xp
-// A batch of at most 1024 pairs (decode) runs steps 1-3 as one workgroup in one launch.
+// A batch of at most 1024 pairs (decode) runs steps 1-2 as one workgroup in one launch; a batch of more than
+// 262144 pairs runs step 2 as a one-workgroup scan kernel followed by the ranking kernel.
 //
-// Steps 1-3 touch only T*k integers; step 4 carries the HBM traffic (T*H*2 bytes read at
+// Steps 1-2 touch only T*k integers; step 3 carries the HBM traffic (T*H*2 bytes read at
 // most, n_local*H*2 written).
 #include <mutex>
 
@@ -28,6 +29,7 @@ constexpr int kPermWaves = 4;                 // waves per workgroup in steps 1 
 constexpr int kSegPairs = 256;                // pairs per wave segment
 constexpr int kSegIters = kSegPairs / kWave;  // 4 wave-wide iterations per segment
 constexpr int kRepLds = 2048;                 // replica-list entries staged in LDS by the index kernel
+constexpr int kFusedBlocks = 256;             // up to this many blocks (262144 pairs) step 2 is one launch
 
 __device__ __forceinline__ uint64_t lanemask_lt() {
   int l = lane_id();
@@ -71,8 +73,11 @@ __global__ __launch_bounds__(kPermWaves* kWave) void permute_hist_kernel(
   }
 }
 
-// Step 2.  One workgroup of 1024 threads: expert e = tid % 256 is scanned by four threads, each
-// over a quarter of the segments (sum pass, then a pass that writes the exclusive bases).
+// Steps 2a / 2b for batches of more than kFusedBlocks blocks, where every workgroup summing all block
+// histograms itself would cost more than a scan kernel in between (the work of step 2 grows with the square
+// of the number of blocks).
+// 2a.  One workgroup of 1024 threads: expert e = tid % 256 is scanned by four threads, each over a quarter
+// of the blocks (sum pass, then a pass that writes the exclusive bases).
 __global__ __launch_bounds__(1024) void permute_scan_kernel(
     int32_t* __restrict__ seg_hist /* in: counts, out: exclusive bases */, int U, int E,
     const int32_t* __restrict__ rep_off, const int32_t* __restrict__ rep_slot,
@@ -186,7 +191,7 @@ __global__ __launch_bounds__(1024) void permute_scan_kernel(
   }
 }
 
-// Step 3.
+// 2b.  Ranks and rows of a block from the exclusive bases and slot offsets written by 2a.
 __global__ __launch_bounds__(kPermWaves* kWave) void permute_index_kernel(
     const int32_t* __restrict__ topk_idx, int N, int E, const int32_t* __restrict__ blk_base,
     const int32_t* __restrict__ rep_off, const int32_t* __restrict__ rep_slot,
@@ -296,7 +301,7 @@ __global__ __launch_bounds__(kPermWaves* kWave) void permute_index_kernel(
   }
 }
 
-// Steps 1-3 in one workgroup, for batches of at most 1024 pairs (decode): the block histogram is the
+// Steps 1-2 in one workgroup, for batches of at most 1024 pairs (decode): the block histogram is the
 // global one, so the scan over blocks disappears and the whole index computation is one launch.
 __global__ __launch_bounds__(kPermWaves* kWave) void permute_small_kernel(
     const int32_t* __restrict__ topk_idx, int N, int E, const int32_t* __restrict__ rep_off,
@@ -447,7 +452,206 @@ __global__ __launch_bounds__(kPermWaves* kWave) void permute_small_kernel(
   }
 }
 
-// Step 4.
+// Step 2: every workgroup sums the block histograms itself (its own exclusive base =
+// the blocks before it, the totals n_e = all blocks), derives the slot counts and offsets from the totals
+// (each workgroup redundantly, workgroup 0 writes them out) and then ranks its own 1024 pairs as above.
+// Reading U*E counters per workgroup costs less than a one-workgroup scan kernel between two launches.
+__global__ __launch_bounds__(kPermWaves* kWave) void permute_scan_index_kernel(
+    const int32_t* __restrict__ topk_idx, int N, int E, const int32_t* __restrict__ blk_hist, int U,
+    const int32_t* __restrict__ rep_off, const int32_t* __restrict__ rep_slot,
+    const int32_t* __restrict__ rep_weight, int S, int32_t* __restrict__ slot_counts,
+    int32_t* __restrict__ slot_offsets, int32_t* __restrict__ n_local, int32_t* __restrict__ pair_row,
+    int32_t* __restrict__ row_pair) {
+  __shared__ int32_t cnt_mem[kPermWaves][PROBE_MAX_EXPERTS];
+  __shared__ int32_t before_mem[kPermWaves][PROBE_MAX_EXPERTS], total_mem[kPermWaves][PROBE_MAX_EXPERTS];
+  __shared__ int32_t e_lo[PROBE_MAX_EXPERTS], e_hi[PROBE_MAX_EXPERTS], e_P[PROBE_MAX_EXPERTS];
+  __shared__ int32_t s_off[PROBE_MAX_SLOTS + 1], sc[PROBE_MAX_SLOTS];
+  __shared__ int32_t s_rw[kRepLds], s_rs[kRepLds];
+  __shared__ int32_t wave_tot[kPermWaves];
+  const int tid = threadIdx.x, w = tid / kWave, lane = lane_id();
+  const int b = blockIdx.x;
+  volatile int32_t* cnt_w = cnt_mem[w];  // volatile: keep every lane's read before the leader's update
+  const long base = (static_cast<long>(b) * kPermWaves + w) * kSegPairs;
+  // loads that depend on nothing first: this wave's pairs, the size of the replica list
+  int seg_e[kSegIters];
+#pragma unroll
+  for (int it = 0; it < kSegIters; ++it) {
+    long p = base + it * kWave + lane;
+    seg_e[it] = p < N ? topk_idx[p] : -1;
+  }
+  const int R = rep_off[E];
+  // block histograms: wave w adds the blocks u = w, w + 4, ... for the experts lane, lane + 64, ...
+  {
+    int before[PROBE_MAX_EXPERTS / kWave], total[PROBE_MAX_EXPERTS / kWave];
+#pragma unroll
+    for (int i = 0; i < PROBE_MAX_EXPERTS / kWave; ++i) before[i] = total[i] = 0;
+    constexpr int kBatch = 16;  // blocks per wave whose loads are in flight together (64 blocks per round)
+    for (int u0 = w; u0 < U; u0 += kBatch * kPermWaves) {
+      int c[kBatch][PROBE_MAX_EXPERTS / kWave];
+#pragma unroll
+      for (int q = 0; q < kBatch; ++q) {
+        const int u = u0 + q * kPermWaves;
+#pragma unroll
+        for (int i = 0; i < PROBE_MAX_EXPERTS / kWave; ++i) {
+          const int e = lane + i * kWave;
+          c[q][i] = (u < U && e < E) ? blk_hist[static_cast<long>(u) * E + e] : 0;
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < kBatch; ++q) {
+        const int u = u0 + q * kPermWaves;
+#pragma unroll
+        for (int i = 0; i < PROBE_MAX_EXPERTS / kWave; ++i) {
+          total[i] += c[q][i];
+          before[i] += u < b ? c[q][i] : 0;
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < PROBE_MAX_EXPERTS / kWave; ++i) {
+      before_mem[w][lane + i * kWave] = before[i];
+      total_mem[w][lane + i * kWave] = total[i];
+    }
+  }
+  const bool staged = R <= kRepLds;
+  if (staged)
+    for (int i = tid; i < R; i += kPermWaves * kWave) {
+      s_rw[i] = rep_weight[i];
+      s_rs[i] = rep_slot[i];
+    }
+  const int32_t* rw = staged ? s_rw : rep_weight;
+  const int32_t* rs = staged ? s_rs : rep_slot;
+  for (int e = tid; e < E; e += kPermWaves * kWave) {
+    e_lo[e] = rep_off[e];
+    e_hi[e] = rep_off[e + 1];
+  }
+  for (int s = tid; s < S; s += kPermWaves * kWave) sc[s] = 0;
+  // counts of this wave's own segment (the same walk as in step 1)
+  for (int e = lane; e < E; e += kWave) cnt_w[e] = 0;
+#pragma unroll
+  for (int it = 0; it < kSegIters; ++it) {
+    int e = seg_e[it];
+    bool valid = static_cast<unsigned>(e) < static_cast<unsigned>(E);
+    uint64_t m = match_key8(e, valid);
+    if (valid && (m & lanemask_lt()) == 0) cnt_w[e] += __popcll(m);
+  }
+  __syncthreads();
+  // rows each replica receives: floor(n/P) w_i + clamp(n mod P - c_{i-1}, 0, w_i)
+  for (int e = tid; e < E; e += kPermWaves * kWave) {
+    int n_e = 0, P = 0;
+#pragma unroll
+    for (int q = 0; q < kPermWaves; ++q) n_e += total_mem[q][e];
+    for (int i = e_lo[e]; i < e_hi[e]; ++i) P += rw[i];
+    e_P[e] = P;
+    if (P > 0) {
+      int full = n_e / P, rem = n_e - full * P, cum = 0;
+      for (int i = e_lo[e]; i < e_hi[e]; ++i) {
+        int wgt = rw[i];
+        int part_rows = min(max(rem - cum, 0), wgt);
+        int slot = rs[i];
+        if (slot >= 0 && slot < S) sc[slot] = full * wgt + part_rows;
+        cum += wgt;
+      }
+    }
+  }
+  __syncthreads();
+  // exclusive prefix sum over the slots, 4 consecutive slots per thread
+  int v[4], local = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    int s = tid * 4 + i;
+    v[i] = s < S ? sc[s] : 0;
+    local += v[i];
+  }
+  int incl = local;
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    int o = __shfl_up(incl, d, kWave);
+    if (lane >= d) incl += o;
+  }
+  if (lane == kWave - 1) wave_tot[w] = incl;
+  __syncthreads();
+  {
+    int excl = incl - local;
+    for (int i = 0; i < w; ++i) excl += wave_tot[i];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int s = tid * 4 + i;
+      if (s < S) {
+        if (b == 0) {
+          slot_counts[s] = v[i];
+          slot_offsets[s] = excl;
+        }
+        s_off[s] = excl;
+      }
+      excl += v[i];
+    }
+    if (tid == kPermWaves * kWave - 1) {
+      if (b == 0) {
+        slot_offsets[S] = excl;
+        n_local[0] = excl;
+      }
+      s_off[S] = excl;
+    }
+  }
+  // arrival rank at the start of this wave's segment: the blocks before this one + the earlier waves
+  int start[PROBE_MAX_EXPERTS / kWave];
+#pragma unroll
+  for (int i = 0; i < PROBE_MAX_EXPERTS / kWave; ++i) {
+    int e = lane + i * kWave;
+    int a = 0;
+    if (e < E) {
+#pragma unroll
+      for (int q = 0; q < kPermWaves; ++q) a += before_mem[q][e];
+      for (int q = 0; q < w; ++q) a += cnt_mem[q][e];
+    }
+    start[i] = a;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < PROBE_MAX_EXPERTS / kWave; ++i) {
+    int e = lane + i * kWave;
+    if (e < E) cnt_w[e] = start[i];
+  }
+  const int n_loc = s_off[S];
+#pragma unroll
+  for (int it = 0; it < kSegIters; ++it) {
+    long p = base + it * kWave + lane;
+    int e = seg_e[it];
+    bool valid = static_cast<unsigned>(e) < static_cast<unsigned>(E);
+    uint64_t m = match_key8(e, valid);
+    if (p < N && !valid) {  // expert id out of range: the pair is computed nowhere on this GPU
+      pair_row[p] = -1;
+      if (p >= n_loc) row_pair[p] = -1;
+    }
+    if (valid) {
+      int before = __popcll(m & lanemask_lt());
+      int j = cnt_w[e] + before;                       // arrival rank of this pair for expert e
+      int lo = e_lo[e], hi = e_hi[e], P = e_P[e];
+      int row = -1;
+      if (P > 0) {
+        int full = j / P, u = j - full * P, cum = 0;
+        for (int i = lo; i < hi; ++i) {
+          int wgt = rw[i];
+          if (u < cum + wgt) {
+            int slot = rs[i];
+            if (slot >= 0 && slot < S) row = s_off[slot] + full * wgt + (u - cum);
+            if (row >= N) row = -1;  // only an inconsistent plan (two replicas in one slot) gets here
+            break;
+          }
+          cum += wgt;
+        }
+      }
+      pair_row[p] = row;
+      if (row >= 0) row_pair[row] = static_cast<int32_t>(p);
+      if (p >= n_loc) row_pair[p] = -1;
+    }
+    // all lanes of a key have read the counter above; the key's first lane now advances it
+    if (valid && (m & lanemask_lt()) == 0) cnt_w[e] += __popcll(m);
+  }
+}
+
+// Step 3.
 template <int K>
 __global__ __launch_bounds__(256) void permute_scatter_kernel(const u32x4* __restrict__ x,
                                                               const int32_t* __restrict__ pair_row,
@@ -498,20 +702,23 @@ static int permute_impl(const char* name, const int32_t* topk_idx, const probe_p
   int N = T * k;
   int U = num_blocks(N);
   int seg_blocks = U;
-  if (U == 1) {
+  if (U <= 1) {
     hipLaunchKernelGGL(permute_small_kernel, dim3(1), dim3(kPermWaves * kWave), 0, st, topk_idx, N, E,
                        plan->rep_off, plan->rep_slot, plan->rep_weight, S, slot_counts, slot_offsets, n_local,
                        pair_row, row_pair);
   } else {
-    if (U > 0)
-      hipLaunchKernelGGL(permute_hist_kernel, dim3(seg_blocks), dim3(kPermWaves * kWave), 0, st, topk_idx, N,
-                         E, seg);
-    hipLaunchKernelGGL(permute_scan_kernel, dim3(1), dim3(1024), 0, st, seg, U, E, plan->rep_off,
-                       plan->rep_slot, plan->rep_weight, S, slot_counts, slot_offsets, n_local);
-    if (U > 0)
-      hipLaunchKernelGGL(permute_index_kernel, dim3(seg_blocks), dim3(kPermWaves * kWave), 0, st, topk_idx,
-                         N, E, seg, plan->rep_off, plan->rep_slot, plan->rep_weight, slot_offsets, S,
-                         pair_row, row_pair);
+    hipLaunchKernelGGL(permute_hist_kernel, dim3(seg_blocks), dim3(kPermWaves * kWave), 0, st, topk_idx, N, E,
+                       seg);
+    if (U <= kFusedBlocks) {
+      hipLaunchKernelGGL(permute_scan_index_kernel, dim3(seg_blocks), dim3(kPermWaves * kWave), 0, st, topk_idx, N,
+                         E, seg, U, plan->rep_off, plan->rep_slot, plan->rep_weight, S, slot_counts, slot_offsets,
+                         n_local, pair_row, row_pair);
+    } else {
+      hipLaunchKernelGGL(permute_scan_kernel, dim3(1), dim3(1024), 0, st, seg, U, E, plan->rep_off,
+                         plan->rep_slot, plan->rep_weight, S, slot_counts, slot_offsets, n_local);
+      hipLaunchKernelGGL(permute_index_kernel, dim3(seg_blocks), dim3(kPermWaves * kWave), 0, st, topk_idx, N, E,
+                         seg, plan->rep_off, plan->rep_slot, plan->rep_weight, slot_offsets, S, pair_row, row_pair);
+    }
   }
   if (U > 0 && xp_bf16 != nullptr) {  // xp == NULL: the caller gathers rows on load instead
     int cpr = H / 8;
