@@ -270,6 +270,23 @@ def main():
     gates = {"predict": 2, "route": 0} if args.fused_route_predict else {"predict": 1, "route": 1}
     gate_tflops = {n: g * 3 * 2.0 * T * H * E / (mean_ms[n] * 1e-3) / 1e12 for n, g in gates.items() if g}
 
+    # The dominant call's roofline: the matrix cores bind when the call's algorithmic intensity (flops per byte of
+    # weights, xp and y) is above the ridge of the nominal peaks (2500 TFLOP/s / 8 TB/s = 312 flop/B); below it
+    # (decode: a few rows per slot) the call is a stream of the active slots' weights and HBM binds.
+    traffic = measured_ffn_traffic(cfg.cid) if nb == min(cfg.n_batches, 8) else None
+    ffn_kernels = ("probe_grouped_ffn (ffn_gemm1_skinny_kernel + ffn_gemm2_skinny_kernel)" if N <= 64 * S else
+                   "probe_grouped_ffn (ffn_gemm1_kernel + ffn_gemm2_kernel)")    # the library's own rule
+    if ffn_flops / ffn_bytes >= PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBPS * 1e9):
+        ffn_roofline = {"kernel": ffn_kernels, "bound": "mfma",
+                        "achieved": ffn_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                        "frac": ffn_tflops / PEAK_BF16_TFLOPS}
+    else:
+        ffn_gbps = ffn_bytes / mean_ms["ffn"] / 1e6
+        ffn_roofline = {"kernel": ffn_kernels, "bound": "hbm", "achieved": ffn_gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                        "frac": ffn_gbps / PEAK_HBM_GBPS}
+    ffn_roofline.update({"traffic": traffic, "algorithmic_flops_per_launch": ffn_flops,
+                         "algorithmic_bytes_per_launch": ffn_bytes, "launch_ms": mean_ms["ffn"]})
+
     result = {
         "metric": "moe_layer_tokens_per_s",
         "value": T * args.steps / elapsed,
@@ -306,12 +323,7 @@ def main():
         "gate_binding_roof": "mfma" if E >= 64 else "hbm",
         "gate_plane_expanded_tflops": gate_tflops,
         "gate_frac_bf16_mfma_peak": {n: v / PEAK_BF16_TFLOPS for n, v in gate_tflops.items()},
-        "roofline": {"kernel": "probe_grouped_ffn (ffn_gemm1_kernel + ffn_gemm2_kernel)", "bound": "mfma",
-                     "achieved": ffn_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": ffn_tflops / PEAK_BF16_TFLOPS,
-                     "traffic": measured_ffn_traffic(cfg.cid) if nb == min(cfg.n_batches, 8) else None,
-                     "algorithmic_flops_per_launch": ffn_flops, "algorithmic_bytes_per_launch": ffn_bytes,
-                     "launch_ms": mean_ms["ffn"]},
+        "roofline": ffn_roofline,
     }
 
     if not args.main_only:
