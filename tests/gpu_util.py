@@ -35,6 +35,18 @@ def rel_err(g: np.ndarray, o: np.ndarray) -> float:
     return float((np.abs(g - o) / (np.abs(o) + rms)).max())
 
 
+def rel_err_rows(g: np.ndarray, o: np.ndarray) -> float:
+    """max over rows t and elements i of |g_ti - o_ti| / (|o_ti| + rms(o_t)): the same metric with the scale taken
+    per row, for tensors whose rows differ in scale by construction (a layer-output row scales with the gate-weight
+    mass of the token's local pairs, which without renormalisation spans more than an order of magnitude)."""
+    if o.size == 0:
+        return 0.0
+    rms = np.sqrt(np.mean(o * o, axis=1, keepdims=True))
+    den = np.abs(o) + rms
+    err = np.abs(g - o)
+    return float(np.where(den > 0, err / np.where(den > 0, den, 1.0), err).max())
+
+
 def ambiguous_tokens(logits: np.ndarray, k: int) -> np.ndarray:
     """Tokens whose k+1 largest logits contain an adjacent gap below TAU."""
     E = logits.shape[1]
@@ -213,13 +225,12 @@ def run_layer_parity(oracle, probe, cfg, batch=0, plan_fn=None, route_sample=Non
         tol = BF16_RTOL * scale + 2.0 ** -8 * np.abs(o_out) + 1e-30
         e_e2e = float((np.abs(g_out - o_out) / tol).max()) * BF16_RTOL
         assert e_e2e <= BF16_RTOL, "layer err %.3e of the propagated FFN tolerance" % e_e2e
-        # and the plain metric max |g - o| / (|o| + rms(o)) on the layer output, over the tokens that have at
-        # least one local pair (a token without one is an exact zero row on both sides and would only dilute
-        # the rms)
-        has_local = (pr >= 0).any(axis=1)
-        if has_local.any():
-            e_out = rel_err(g_out[has_local], o_out[has_local])
-            assert e_out <= BF16_RTOL, "layer output rel err %.3e" % e_out
+        # and the plain metric on the layer output with the scale of each token's own row,
+        # max |g - o| / (|o| + rms(o[t])): a row of `out` scales with the gate-weight mass of the token's local pairs
+        # (zero for a token without one, and spread over more than an order of magnitude without renormalisation),
+        # so one rms over the whole tensor is not the scale of any row
+        e_out = rel_err_rows(g_out, o_out)
+        assert e_out <= BF16_RTOL, "layer output rel err %.3e" % e_out
     res = dict(cfg=cfg.name, batch=batch, n_local=nl, ambiguous=n_amb, ffn_err=e_ffn, combine_err=e_comb,
                e2e_err=e_e2e, out_err=e_out, sampled_rows=int(len(rows)), slot_rows=o_p["slot_counts"].tolist())
     if report is not None:
