@@ -316,7 +316,21 @@ __global__ __launch_bounds__(kPermWaves* kWave) void permute_small_kernel(
   const int tid = threadIdx.x, w = tid / kWave, lane = lane_id();
   volatile int32_t* cnt_w = cnt_mem[w];  // volatile: keep every lane's read before the leader's update
   const long base = static_cast<long>(w) * kSegPairs;
+  // The kernel is a chain of dependent global loads, so every load that depends on nothing is issued first: the
+  // segment's expert ids, the size of the replica list and this thread's replica range (E <= 256 = threads).
+  static_assert(kPermWaves * kWave >= PROBE_MAX_EXPERTS, "one expert per thread");
+  int seg_e[kSegIters];
+#pragma unroll
+  for (int it = 0; it < kSegIters; ++it) {
+    const long p = base + it * kWave + lane;
+    seg_e[it] = p < N ? topk_idx[p] : -1;
+  }
   const int R = rep_off[E];
+  int my_lo = 0, my_hi = 0;
+  if (tid < E) {
+    my_lo = rep_off[tid];
+    my_hi = rep_off[tid + 1];
+  }
   const bool staged = R <= kRepLds;
   if (staged)
     for (int i = tid; i < R; i += kPermWaves * kWave) {
@@ -325,22 +339,19 @@ __global__ __launch_bounds__(kPermWaves* kWave) void permute_small_kernel(
     }
   const int32_t* rw = staged ? s_rw : rep_weight;
   const int32_t* rs = staged ? s_rs : rep_slot;
-  for (int e = tid; e < E; e += kPermWaves * kWave) {
-    int lo = rep_off[e], hi = rep_off[e + 1], P = 0;
-    for (int i = lo; i < hi; ++i) P += rep_weight[i];
-    e_lo[e] = lo;
-    e_hi[e] = hi;
-    e_P[e] = P;
+  if (tid < E) {
+    int P = 0;
+    for (int i = my_lo; i < my_hi; ++i) P += rep_weight[i];
+    e_lo[tid] = my_lo;
+    e_hi[tid] = my_hi;
+    e_P[tid] = P;
   }
   for (int s = tid; s < S; s += kPermWaves * kWave) sc[s] = 0;
   // counts of this wave's segment
   for (int e = lane; e < E; e += kWave) cnt_w[e] = 0;
-  int seg_e[kSegIters];
 #pragma unroll
   for (int it = 0; it < kSegIters; ++it) {
-    long p = base + it * kWave + lane;
-    int e = p < N ? topk_idx[p] : -1;
-    seg_e[it] = e;
+    const int e = seg_e[it];
     bool valid = static_cast<unsigned>(e) < static_cast<unsigned>(E);
     uint64_t m = match_key8(e, valid);
     if (valid && (m & lanemask_lt()) == 0) cnt_w[e] += __popcll(m);
