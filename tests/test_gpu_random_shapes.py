@@ -90,3 +90,17 @@ def test_random_shape_and_plan(oracle, probe, G, case, T, H, E, k, F, zipf_s, ch
     plan = random_plan(rng, E, max_slots=max_slots)
     res = G.run_layer_parity(oracle, probe, cfg, batch=0, plan_fn=lambda c, counts: plan, renormalize=bool(case % 2))
     assert res["n_local"] <= T * k
+
+
+@pytest.mark.parametrize("case,T,H,E,k,F,max_slots", [(0, 6001, 256, 8, 6, 1024, 24), (1, 8192, 320, 16, 8, 512, 60),
+                                                       (2, 4096, 512, 4, 3, 1536, 4)])
+def test_every_element_on_the_work_queue_path(oracle, probe, G, case, T, H, E, k, F, max_slots):
+    """Mid-size layers with tens of thousands of local rows: the FFN runs as the persistent launch (more work items
+    than CUs, tickets drawn from the per-XCD counters, stealing at the end) and EVERY element of h's consumer y and of
+    the layer output is compared with the oracle, not a sample."""
+    print("case queue %d: T=%d H=%d E=%d k=%d F=%d slots<=%d" % (case, T, H, E, k, F, max_slots), flush=True)
+    cfg = wl.small_config(T=T, H=H, E=E, k=k, F=F, E_loc=min(E, 4), n_rep=0, zipf_s=1.0, chunk=0, ep=1,
+                          cid=400 + case)
+    plan = random_plan(np.random.default_rng(9000 + case), E, max_slots=max_slots)
+    res = G.run_layer_parity(oracle, probe, cfg, batch=0, plan_fn=lambda c, counts: plan, renormalize=True)
+    assert res["sampled_rows"] == res["n_local"] and res["n_local"] >= 4096
