@@ -255,25 +255,36 @@ struct WorkQueue {
     victim = __builtin_amdgcn_s_getreg((20 << 0) | (0 << 6) | (3 << 11)) & (kXcds - 1);  // XCC_ID
     misses = 0;
   }
-  // all threads of the workgroup call this together; *slot is one int of static LDS
-  __device__ __forceinline__ bool next(int n_tiles, int n_cols, int* slot, int& tile, int& col) {
+  // What ticket t of counter `victim` stands for; false (and the bookkeeping of an unsuccessful draw) if nothing.
+  __device__ __forceinline__ bool accept(int t, int n_tiles, int n_cols, int& tile, int& col) {
     const int col_groups = (n_cols + kBlkN - 1) / kBlkN, tile_groups = (n_tiles + kBlkM - 1) / kBlkM;
-    const int n_blocks = tile_groups * col_groups;
+    const int b = (t / kBlk) * kXcds + victim;
+    if (b >= tile_groups * col_groups) {  // this XCD's blocks are used up: go on to the next one's
+      victim = (victim + 1) & (kXcds - 1);
+      ++misses;
+      return false;
+    }
+    misses = 0;
+    return ffn_item_of(b * kBlk + t % kBlk, n_tiles, n_cols, tile, col);
+  }
+  // all threads of the workgroup call this together; *slot is one int of static LDS
+  __device__ __forceinline__ bool next(int n_tiles, int n_cols, volatile int* slot, int& tile, int& col) {
     while (misses < kXcds) {
       __syncthreads();  // the previous item is finished by every wave (LDS stages, *slot)
       if (threadIdx.x == 0) *slot = atomicAdd(&counters[victim], 1);
       __syncthreads();
-      const int t = *slot;
-      const int b = (t / kBlk) * kXcds + victim;
-      if (b >= n_blocks) {  // this XCD's blocks are used up: go on to the next one's
-        victim = (victim + 1) & (kXcds - 1);
-        ++misses;
-        continue;
-      }
-      misses = 0;
-      if (ffn_item_of(b * kBlk + t % kBlk, n_tiles, n_cols, tile, col)) return true;
+      if (accept(__builtin_amdgcn_readfirstlane(*slot), n_tiles, n_cols, tile, col)) return true;
     }
     return false;
+  }
+  // The same when thread 0 has already drawn a ticket during the last k-steps of the previous item (gemm_mainloop,
+  // DRAW) and every wave is past that loop's last barrier: no barrier is needed to read it, and none before the next
+  // item's loads either, because no wave reads the LDS stages after that barrier.  Falls back to next() when the
+  // ticket names no item (the end of a queue).
+  __device__ __forceinline__ bool next_drawn(bool drew, int n_tiles, int n_cols, volatile int* slot, int& tile,
+                                             int& col) {
+    if (drew && accept(__builtin_amdgcn_readfirstlane(*slot), n_tiles, n_cols, tile, col)) return true;
+    return next(n_tiles, n_cols, slot, tile, col);
   }
 };
 
@@ -294,10 +305,11 @@ struct RowSource {
 
 // NI = 32-row weight fragments per wave: 2 = a column block of 128 h columns (128 gate + 128 up weight
 // rows per workgroup), 1 = 64 h columns (the skinny tiles of the decode schedule).  NST = LDS stages.
-template <int MI, bool GATHER, int NI = 2, int NST = (MI >= 3 ? 2 : 3)>
-__device__ __forceinline__ void gemm1_tile(const RowSource& src, const bf16_t* __restrict__ w13,
+template <int MI, bool GATHER, int NI = 2, int NST = (MI >= 3 ? 2 : 3), bool DRAW = false>
+__device__ __forceinline__ bool gemm1_tile(const RowSource& src, const bf16_t* __restrict__ w13,
                                            int row0, int rows, int n0, int H, int F,
-                                           bf16_t* __restrict__ hbuf, u32x4* smem) {
+                                           bf16_t* __restrict__ hbuf, u32x4* smem, int32_t* draw_counter = nullptr,
+                                           volatile int* draw_slot = nullptr) {
   // rows = valid rows from row0 to the end of the slot (may exceed the tile height)
   constexpr int HALF = 16 * NI;  // h columns per wave; its 32*NI weight rows are HALF gate rows, then the HALF up rows
   const int lane = threadIdx.x & 63;
@@ -326,7 +338,8 @@ __device__ __forceinline__ void gemm1_tile(const RowSource& src, const bf16_t* _
                       voff + MI);
   f32x16 acc[MI][NI];
   zero_acc<MI, NI>(acc);
-  gemm_mainloop<MI, NI, 1, NST, true>(rA, rB, voff, 0, H, smem, wv, lane, acc);
+  const bool drew =
+      gemm_mainloop<MI, NI, 1, NST, true, DRAW>(rA, rB, voff, 0, H, smem, wv, lane, acc, draw_counter, draw_slot);
 
   // Accumulator registers 8g .. 8g+7 of a lane are eight consecutive output columns of one output
   // row (see gemm_mainloop, PERM): one 16-byte store each.  The stores go through a buffer
@@ -359,6 +372,7 @@ __device__ __forceinline__ void gemm1_tile(const RowSource& src, const bf16_t* _
       }
     }
   }
+  return drew;
 }
 
 // one-dimensional launch over (row tile, column block) work items; a column block is 128 gate +
@@ -372,34 +386,55 @@ __global__ __launch_bounds__(512, 2) void ffn_gemm1_kernel(RowSource src, const 
   extern __shared__ u32x4 smem[];
   __shared__ int ticket;
   const int n_tiles = table[0], n_cols = (F + 127) / 128;
-  WorkQueue wq;
-  if (queue) wq.init(table_rw + kQueue1);
   int tile, col;
-  if (!queue && !ffn_work_item(n_tiles, n_cols, tile, col)) return;
-  while (!queue || wq.next(n_tiles, n_cols, &ticket, tile, col)) {
-    const TileEntry e = reinterpret_cast<const TileEntry*>(table + kTableHeaderInts)[tile];
-    const int n0 = col * 128;
-    const bf16_t* w13 = static_cast<const bf16_t*>(e.w13);
-    if (e.height > 256)
-      gemm1_tile<5, GATHER>(src, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
-    else if (e.height > 192)
-      gemm1_tile<4, GATHER>(src, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
-    else if (e.height > 128)
-      gemm1_tile<3, GATHER>(src, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
-    else if (e.height > 64)
-      gemm1_tile<2, GATHER>(src, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
-    else
-      gemm1_tile<1, GATHER>(src, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
-    if (!queue) break;
+  if (queue) {
+    // persistent launch: the ticket of the next item is drawn while the last k-steps of this one run
+    WorkQueue wq;
+    wq.init(table_rw + kQueue1);
+    bool more = wq.next(n_tiles, n_cols, &ticket, tile, col);
+    while (more) {
+      const TileEntry e = reinterpret_cast<const TileEntry*>(table + kTableHeaderInts)[tile];
+      const int n0 = col * 128;
+      const bf16_t* w13 = static_cast<const bf16_t*>(e.w13);
+      int32_t* ctr = wq.counters + wq.victim;
+      bool drew;
+      if (e.height > 256)
+        drew = gemm1_tile<5, GATHER, 2, 2, true>(src, w13, e.row0, e.rows, n0, H, F, hbuf, smem, ctr, &ticket);
+      else if (e.height > 192)
+        drew = gemm1_tile<4, GATHER, 2, 2, true>(src, w13, e.row0, e.rows, n0, H, F, hbuf, smem, ctr, &ticket);
+      else if (e.height > 128)
+        drew = gemm1_tile<3, GATHER, 2, 2, true>(src, w13, e.row0, e.rows, n0, H, F, hbuf, smem, ctr, &ticket);
+      else if (e.height > 64)
+        drew = gemm1_tile<2, GATHER, 2, 3, true>(src, w13, e.row0, e.rows, n0, H, F, hbuf, smem, ctr, &ticket);
+      else
+        drew = gemm1_tile<1, GATHER, 2, 3, true>(src, w13, e.row0, e.rows, n0, H, F, hbuf, smem, ctr, &ticket);
+      more = wq.next_drawn(drew, n_tiles, n_cols, &ticket, tile, col);
+    }
+    return;
   }
+  if (!ffn_work_item(n_tiles, n_cols, tile, col)) return;
+  const TileEntry e = reinterpret_cast<const TileEntry*>(table + kTableHeaderInts)[tile];
+  const int n0 = col * 128;
+  const bf16_t* w13 = static_cast<const bf16_t*>(e.w13);
+  if (e.height > 256)
+    gemm1_tile<5, GATHER>(src, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
+  else if (e.height > 192)
+    gemm1_tile<4, GATHER>(src, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
+  else if (e.height > 128)
+    gemm1_tile<3, GATHER>(src, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
+  else if (e.height > 64)
+    gemm1_tile<2, GATHER>(src, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
+  else
+    gemm1_tile<1, GATHER>(src, w13, e.row0, e.rows, n0, H, F, hbuf, smem);
 #endif
 }
 
 // ---- 2. gemm2 -------------------------------------------------------------------------
-template <int MI, int NI = 2, int NST = (MI >= 3 ? 2 : 3)>
-__device__ __forceinline__ void gemm2_tile(const bf16_t* __restrict__ hbuf, const bf16_t* __restrict__ w2,
+template <int MI, int NI = 2, int NST = (MI >= 3 ? 2 : 3), bool DRAW = false>
+__device__ __forceinline__ bool gemm2_tile(const bf16_t* __restrict__ hbuf, const bf16_t* __restrict__ w2,
                                            int row0, int rows, int n0, int H, int F,
-                                           bf16_t* __restrict__ y, u32x4* smem) {
+                                           bf16_t* __restrict__ y, u32x4* smem, int32_t* draw_counter = nullptr,
+                                           volatile int* draw_slot = nullptr) {
   const int lane = threadIdx.x & 63;
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wv / 4, wn = wv % 4;
@@ -410,7 +445,8 @@ __device__ __forceinline__ void gemm2_tile(const bf16_t* __restrict__ hbuf, cons
   dma_offsets<2 * NI>(wv, lane, F * 2, [&](int j) { return min(n0 + j, H - 1); }, voff + MI);
   f32x16 acc[MI][NI];
   zero_acc<MI, NI>(acc);
-  gemm_mainloop<MI, NI, 1, NST, true>(rA, rB, voff, 0, F, smem, wv, lane, acc);
+  const bool drew =
+      gemm_mainloop<MI, NI, 1, NST, true, DRAW>(rA, rB, voff, 0, F, smem, wv, lane, acc, draw_counter, draw_slot);
 
   const int valid = min(rows, 64 * MI);  // rows past it are dropped by the descriptor's bounds check
   __amdgpu_buffer_rsrc_t rY = make_rsrc(y + static_cast<size_t>(row0) * H, static_cast<size_t>(valid) * H * 2);
@@ -434,6 +470,7 @@ __device__ __forceinline__ void gemm2_tile(const bf16_t* __restrict__ hbuf, cons
       }
     }
   }
+  return drew;
 }
 
 // one-dimensional launch over (row tile, column block of 256 output columns) work items
@@ -444,26 +481,45 @@ __global__ __launch_bounds__(512, 2) void ffn_gemm2_kernel(const bf16_t* __restr
   extern __shared__ u32x4 smem[];
   __shared__ int ticket;
   const int n_tiles = table[0], n_cols = (H + FBN - 1) / FBN;
-  WorkQueue wq;
-  if (queue) wq.init(table_rw + kQueue2);
   int tile, col;
-  if (!queue && !ffn_work_item(n_tiles, n_cols, tile, col)) return;
-  while (!queue || wq.next(n_tiles, n_cols, &ticket, tile, col)) {
-    const TileEntry e = reinterpret_cast<const TileEntry*>(table + kTableHeaderInts)[tile];
-    const int n0 = col * FBN;
-    const bf16_t* w2 = static_cast<const bf16_t*>(e.w2);
-    if (e.height > 256)
-      gemm2_tile<5>(hbuf, w2, e.row0, e.rows, n0, H, F, y, smem);
-    else if (e.height > 192)
-      gemm2_tile<4>(hbuf, w2, e.row0, e.rows, n0, H, F, y, smem);
-    else if (e.height > 128)
-      gemm2_tile<3>(hbuf, w2, e.row0, e.rows, n0, H, F, y, smem);
-    else if (e.height > 64)
-      gemm2_tile<2>(hbuf, w2, e.row0, e.rows, n0, H, F, y, smem);
-    else
-      gemm2_tile<1>(hbuf, w2, e.row0, e.rows, n0, H, F, y, smem);
-    if (!queue) break;
+  if (queue) {
+    WorkQueue wq;
+    wq.init(table_rw + kQueue2);
+    bool more = wq.next(n_tiles, n_cols, &ticket, tile, col);
+    while (more) {
+      const TileEntry e = reinterpret_cast<const TileEntry*>(table + kTableHeaderInts)[tile];
+      const int n0 = col * FBN;
+      const bf16_t* w2 = static_cast<const bf16_t*>(e.w2);
+      int32_t* ctr = wq.counters + wq.victim;
+      bool drew;
+      if (e.height > 256)
+        drew = gemm2_tile<5, 2, 2, true>(hbuf, w2, e.row0, e.rows, n0, H, F, y, smem, ctr, &ticket);
+      else if (e.height > 192)
+        drew = gemm2_tile<4, 2, 2, true>(hbuf, w2, e.row0, e.rows, n0, H, F, y, smem, ctr, &ticket);
+      else if (e.height > 128)
+        drew = gemm2_tile<3, 2, 2, true>(hbuf, w2, e.row0, e.rows, n0, H, F, y, smem, ctr, &ticket);
+      else if (e.height > 64)
+        drew = gemm2_tile<2, 2, 3, true>(hbuf, w2, e.row0, e.rows, n0, H, F, y, smem, ctr, &ticket);
+      else
+        drew = gemm2_tile<1, 2, 3, true>(hbuf, w2, e.row0, e.rows, n0, H, F, y, smem, ctr, &ticket);
+      more = wq.next_drawn(drew, n_tiles, n_cols, &ticket, tile, col);
+    }
+    return;
   }
+  if (!ffn_work_item(n_tiles, n_cols, tile, col)) return;
+  const TileEntry e = reinterpret_cast<const TileEntry*>(table + kTableHeaderInts)[tile];
+  const int n0 = col * FBN;
+  const bf16_t* w2 = static_cast<const bf16_t*>(e.w2);
+  if (e.height > 256)
+    gemm2_tile<5>(hbuf, w2, e.row0, e.rows, n0, H, F, y, smem);
+  else if (e.height > 192)
+    gemm2_tile<4>(hbuf, w2, e.row0, e.rows, n0, H, F, y, smem);
+  else if (e.height > 128)
+    gemm2_tile<3>(hbuf, w2, e.row0, e.rows, n0, H, F, y, smem);
+  else if (e.height > 64)
+    gemm2_tile<2>(hbuf, w2, e.row0, e.rows, n0, H, F, y, smem);
+  else
+    gemm2_tile<1>(hbuf, w2, e.row0, e.rows, n0, H, F, y, smem);
 #endif
 }
 

@@ -33,10 +33,16 @@ __device__ __forceinline__ void wait_vm_lgkm0() {  // s_waitcnt vmcnt(N) lgkmcnt
 // 16g + 8(l / 32) .. +7, a 16-byte bf16 store per lane and 32 contiguous bytes per row and store
 // instruction.  Sixteen consecutive positions still read sixteen consecutive LDS rows, so the
 // fragment reads stay free of bank conflicts.
-template <int MI, int NI, int PL, int NST, bool PERM = false>
-__device__ __forceinline__ void gemm_mainloop(__amdgpu_buffer_rsrc_t rA, __amdgpu_buffer_rsrc_t rB,
+//
+// DRAW: thread 0 of the workgroup draws the next ticket of a work queue (atomic add of 1 on *draw_counter) at the
+// start of the second-to-last k-step, which issues no DMA and ends with a wait for everything in flight, and
+// leaves it in *draw_slot (LDS) before that step's barrier; after the loop every thread can read it.  Returns
+// whether that happened (it needs K >= 128).  After the barrier of the last k-step no wave reads the LDS stages.
+template <int MI, int NI, int PL, int NST, bool PERM = false, bool DRAW = false>
+__device__ __forceinline__ bool gemm_mainloop(__amdgpu_buffer_rsrc_t rA, __amdgpu_buffer_rsrc_t rB,
                                               const int (&voff)[MI + NI * PL * 2], int k0, int K,
-                                              u32x4* smem, int wv, int lane, f32x16 (&acc)[MI][NI]) {
+                                              u32x4* smem, int wv, int lane, f32x16 (&acc)[MI][NI],
+                                              int32_t* draw_counter = nullptr, volatile int* draw_slot = nullptr) {
   constexpr int WN = 4, BROWS = 128 * NI * PL, AW = MI, BW = BROWS / 64, LPW = AW + BW, BM = 64 * MI;
   constexpr int NB = NI * PL;             // B fragments per k16
   constexpr int kStage = (BM + BROWS) * 8;  // 16-byte units per stage
@@ -109,7 +115,8 @@ __device__ __forceinline__ void gemm_mainloop(__amdgpu_buffer_rsrc_t rA, __amdgp
   // One k-step on stage `cur`.  DMA: issue tile kt+NST into the stage being vacated.
   // YOUNGER: a batch younger than tile kt+1 is in flight at the barrier (it may stay in flight).
   // NEXT: tile kt+1 exists.
-  auto k_step = [&](int kt, int cur, auto dma_c, auto younger_c, auto next_c) {
+  // `hook` runs between the step's wait and its barrier (LDS writes made there are seen by every wave after it).
+  auto k_step = [&](int kt, int cur, auto dma_c, auto younger_c, auto next_c, auto hook) {
     constexpr bool DMA = decltype(dma_c)::value, YOUNGER = decltype(younger_c)::value,
                    NEXT = decltype(next_c)::value;
     const int nxt = (cur + 1 == NST) ? 0 : cur + 1;
@@ -131,6 +138,7 @@ __device__ __forceinline__ void gemm_mainloop(__amdgpu_buffer_rsrc_t rA, __amdgp
     __builtin_amdgcn_sched_barrier(0);
     // every read of stage cur is issued: wait for them and for this wave's share of tile kt+1
     if constexpr (YOUNGER) wait_vm_lgkm0<LPW>(); else wait_vm_lgkm0<0>();
+    hook();
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     if constexpr (NEXT) read_frags(nxt, 0, a0, b0);
@@ -161,30 +169,46 @@ __device__ __forceinline__ void gemm_mainloop(__amdgpu_buffer_rsrc_t rA, __amdgp
     ++kt;
     cur = (cur + 1 == NST) ? 0 : cur + 1;
   };
+  auto none = []() {};
+  bool drew = false;
+  auto step_before_last = [&]() {
+    if constexpr (DRAW) {
+      int ticket = 0;
+      if (threadIdx.x == 0) ticket = atomicAdd(draw_counter, 1);
+      k_step(kt, cur, F_{}, F_{}, T_{}, [&]() {
+        if (threadIdx.x == 0) *draw_slot = ticket;
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the write has landed before the barrier
+      });
+      drew = true;
+    } else {
+      k_step(kt, cur, F_{}, F_{}, T_{}, none);
+    }
+  };
   if constexpr (NST == 2) {
     while (kt + 2 < KT) {
-      k_step(kt, cur, T_{}, F_{}, T_{});
+      k_step(kt, cur, T_{}, F_{}, T_{}, none);
       advance();
     }
     if (kt + 1 < KT) {
-      k_step(kt, cur, F_{}, F_{}, T_{});
+      step_before_last();
       advance();
     }
   } else {
     while (kt + 3 < KT) {
-      k_step(kt, cur, T_{}, T_{}, T_{});
+      k_step(kt, cur, T_{}, T_{}, T_{}, none);
       advance();
     }
     if (kt + 2 < KT) {
-      k_step(kt, cur, F_{}, T_{}, T_{});
+      k_step(kt, cur, F_{}, T_{}, T_{}, none);
       advance();
     }
     if (kt + 1 < KT) {
-      k_step(kt, cur, F_{}, F_{}, T_{});
+      step_before_last();
       advance();
     }
   }
-  k_step(kt, cur, F_{}, F_{}, F_{});
+  k_step(kt, cur, F_{}, F_{}, F_{}, none);
+  return drew;
 }
 
 // Raw buffer descriptor over [base, base + bytes): loads past the end return zero.
