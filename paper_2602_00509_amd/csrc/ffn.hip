@@ -322,9 +322,11 @@ __device__ __forceinline__ bool gemm1_tile(const RowSource& src, const bf16_t* _
   int voff[MI + 2 * NI];
   dma_offsets<MI>(wv, lane, H * 2,
                   [&](int r) {
-                    const int rr = min(r, rows - 1);
-                    if (!GATHER) return rr;
-                    const int pair = src.row_pair[row0 + rr];  // a valid row always names a pair
+                    // a tile row past the slot's last row gets an offset past the end of the descriptor: the
+                    // load returns zeros, which also cost the matrix cores less than a copy of a real row
+                    if (!GATHER) return r;
+                    if (r >= rows) return src.n_tokens;
+                    const int pair = src.row_pair[row0 + r];  // a valid row always names a pair
                     return min(max(pair, 0) / src.k, src.n_tokens - 1);
                   },
                   voff);
@@ -441,7 +443,7 @@ __device__ __forceinline__ bool gemm2_tile(const bf16_t* __restrict__ hbuf, cons
   __amdgpu_buffer_rsrc_t rA = make_rsrc(hbuf + static_cast<size_t>(row0) * F, static_cast<size_t>(rows) * F * 2);
   __amdgpu_buffer_rsrc_t rB = make_rsrc(w2, static_cast<size_t>(H) * F * 2);
   int voff[MI + 2 * NI];
-  dma_offsets<MI>(wv, lane, F * 2, [&](int r) { return min(r, rows - 1); }, voff);
+  dma_offsets<MI>(wv, lane, F * 2, [&](int r) { return r; }, voff);  // rows past the slot read as zeros (out of range)
   dma_offsets<2 * NI>(wv, lane, F * 2, [&](int j) { return min(n0 + j, H - 1); }, voff + MI);
   f32x16 acc[MI][NI];
   zero_acc<MI, NI>(acc);
