@@ -22,8 +22,9 @@
 //
 // In gemm1 a workgroup's 256 weight rows are 128 gate rows plus the 128 matching up rows,
 // arranged so that each lane holds gate and up of the same output element; SwiGLU is applied
-// on the accumulators.  Ragged row counts are handled by clamping the row a lane loads to
-// the slot's last row and masking stores; the row space is never padded.
+// on the accumulators.  Ragged row counts: a tile row past the slot's last row lies past the end
+// of the activation tile's buffer descriptor, so its loads return zeros, and its stores are
+// dropped the same way; the row space is never padded.
 #include <mutex>
 
 #include "common.hpp"
